@@ -1,0 +1,255 @@
+/* CPU oracle for batched DLRM-style inference.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, by-the-definition implementation of what the GPU library
+ * computes, written from the model description in Section II-A of the
+ * DeepRecSys paper ("Key Components in Neural Recommendation Models") and the
+ * shape table (Table I).  It shares no code with the GPU path.  Only tests, the
+ * smoke check and the benchmark's CPU-baseline leg may call it; the product
+ * never does.
+ *
+ * All floating-point sums are accumulated in fp64 and rounded once to fp32,
+ * unless a function says otherwise.  Loops run in the order the definition
+ * states; there is no blocking, vectorisation or fusion.  The only concession
+ * to run time is an OpenMP "parallel for" over independent samples or bags
+ * (the request-level parallelism of Section IV-A), which does not change any
+ * result.
+ *
+ * Every function here is pinned by tests that do not use the function itself:
+ * hand-computed bags, closed forms, invariants and NumPy / PyTorch-CPU library
+ * routines.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_OK = 0, ORC_ERR_NULL = 1, ORC_ERR_BAD_SHAPE = 2, ORC_ERR_NEGATIVE_LENGTH = 3,
+       ORC_ERR_LENGTHS_MISMATCH = 4, ORC_ERR_INDEX_RANGE = 5 };
+enum { ORC_ACT_NONE = 0, ORC_ACT_RELU = 1, ORC_ACT_SIGMOID = 2 };
+
+static int g_threads = 1;
+
+void orc_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+
+int orc_get_threads(void) {
+#ifdef _OPENMP
+    return g_threads;
+#else
+    return 1;
+#endif
+}
+
+/* Round an fp32 value to the nearest bf16 (ties to even), returned as fp32.
+ * bf16 keeps the top 16 bits of the fp32 pattern.  NaN stays NaN. */
+float orc_bf16_round(float x) {
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+        u |= 0x00400000u;           /* quiet the NaN, keep it a NaN */
+        u &= 0xffff0000u;
+    } else {
+        uint32_t lsb = (u >> 16) & 1u;
+        u += 0x7fffu + lsb;
+        u &= 0xffff0000u;
+    }
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+void orc_bf16_round_array(const float* x, float* y, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) y[i] = orc_bf16_round(x[i]);
+}
+
+/* Input check for the sparse side (Section II-A, "Embedding Table Access": the
+ * sparse inputs index into specific rows of their table).  Bags are table-major:
+ * bag t*B+b holds the lookups of sample b into table t.
+ *   - every length >= 0                       else ORC_ERR_NEGATIVE_LENGTH
+ *   - sum of lengths (64-bit) == n_indices    else ORC_ERR_LENGTHS_MISMATCH
+ *   - every index of table t in [0, rows[t])  else ORC_ERR_INDEX_RANGE
+ * n_bad = number of out-of-range indices, first_bad = flat position of the
+ * first one (-1 if none); both are only meaningful when the first two checks
+ * pass. */
+int orc_validate(const int64_t* rows, int32_t T, const int32_t* indices, int64_t n_indices,
+                 const int32_t* lengths, int32_t B, int64_t* n_bad, int64_t* first_bad) {
+    *n_bad = 0;
+    *first_bad = -1;
+    int64_t total = 0;
+    for (int64_t i = 0; i < (int64_t)T * B; ++i) {
+        if (lengths[i] < 0) return ORC_ERR_NEGATIVE_LENGTH;
+        total += lengths[i];
+    }
+    if (total != n_indices) return ORC_ERR_LENGTHS_MISMATCH;
+    int64_t pos = 0;
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t k = 0; k < lengths[(int64_t)t * B + b]; ++k, ++pos)
+                if (indices[pos] < 0 || (int64_t)indices[pos] >= rows[t]) {
+                    if (*n_bad == 0) *first_bad = pos;
+                    ++*n_bad;
+                }
+    return *n_bad ? ORC_ERR_INDEX_RANGE : ORC_OK;
+}
+
+/* Exclusive prefix sum of the bag lengths: off[0] = 0, off[i+1] = off[i] + lengths[i]. */
+void orc_offsets(const int32_t* lengths, int64_t n_bags, int64_t* off) {
+    off[0] = 0;
+    for (int64_t i = 0; i < n_bags; ++i) off[i + 1] = off[i] + lengths[i];
+}
+
+/* Embedding lookup with sum pooling (Section II-A, "Embedding Table Access";
+ * Table I, pooling = Sum): for bag (t, b)
+ *     E[b][t][:] = sum over k < L  of  Table_t[ idx[off + k] ][:]
+ * unweighted, duplicates counted as often as they occur, empty bag -> zeros.
+ * Element (b, t, d) is written to out[b*stride_b + t*stride_t + d].
+ *   out       fp64-accumulated sum rounded once to fp32 (the reference value)
+ *   out_seq   optional: plain fp32 running sum in lookup order
+ *   out_abs   optional: fp64 sum of |x|, same addressing as out, for error bounds */
+void orc_sls(const float* const* tables, int32_t T, int32_t D, const int32_t* indices,
+             const int64_t* off, int32_t B, float* out, int64_t stride_b, int64_t stride_t,
+             float* out_seq, double* out_abs) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int32_t b = 0; b < B; ++b) {
+        double* acc = (double*)malloc(sizeof(double) * D * 2);
+        float* seq = (float*)malloc(sizeof(float) * D);
+        double* aabs = acc + D;
+        for (int32_t t = 0; t < T; ++t) {
+            const int64_t bag = (int64_t)t * B + b;
+            for (int32_t d = 0; d < D; ++d) { acc[d] = 0.0; aabs[d] = 0.0; seq[d] = 0.0f; }
+            for (int64_t p = off[bag]; p < off[bag + 1]; ++p) {
+                const float* row = tables[t] + (int64_t)indices[p] * D;
+                for (int32_t d = 0; d < D; ++d) {
+                    acc[d] += (double)row[d];
+                    aabs[d] += fabs((double)row[d]);
+                    seq[d] = seq[d] + row[d];
+                }
+            }
+            const int64_t o = b * stride_b + t * stride_t;
+            for (int32_t d = 0; d < D; ++d) {
+                out[o + d] = (float)acc[d];
+                if (out_seq) out_seq[o + d] = seq[d];
+                if (out_abs) out_abs[o + d] = aabs[d];
+            }
+        }
+        free(acc);
+        free(seq);
+    }
+}
+
+static float apply_act(double z, int act) {
+    if (act == ORC_ACT_RELU) return (float)(z > 0.0 ? z : 0.0);
+    if (act == ORC_ACT_SIGMOID) return (float)(1.0 / (1.0 + exp(-z)));
+    return (float)z;
+}
+
+/* One fully-connected layer (Section II-A, "Features": dense inputs go through a
+ * stack of fully-connected layers; "Product Ranking": the predictor stack ends
+ * in a click probability):
+ *     y[b][o] = act( bias[o] + sum_i x[b][i] * W[o][i] )
+ * W is [n_out][n_in] row-major.  With bf16_operands != 0, x and W are first
+ * rounded to bf16 (ties to even).  Products, the sum, the bias add and the
+ * activation are all evaluated in fp64; the result is rounded once to fp32. */
+void orc_fc(const float* x, int64_t ldx, const float* W, const float* bias, int32_t B,
+            int32_t n_in, int32_t n_out, int32_t act, int32_t bf16_operands, float* y, int64_t ldy) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t o = 0; o < n_out; ++o) {
+            double acc = 0.0;
+            for (int32_t i = 0; i < n_in; ++i) {
+                float xv = x[b * ldx + i], wv = W[(int64_t)o * n_in + i];
+                if (bf16_operands) { xv = orc_bf16_round(xv); wv = orc_bf16_round(wv); }
+                acc += (double)xv * (double)wv;
+            }
+            y[b * ldy + o] = apply_act(acc + (double)bias[o], act);
+        }
+    }
+}
+
+/* A stack of FC layers: hidden layers use hidden_act, the last uses final_act.
+ * W[l] is [widths[l+1]][widths[l]].  Activations between layers are fp32. */
+void orc_mlp(const float* const* W, const float* const* bias, const int32_t* widths,
+             int32_t n_layers, int32_t bf16_operands, int32_t hidden_act, int32_t final_act,
+             const float* x, int64_t ldx, float* y, int64_t ldy, int32_t B) {
+    const float* cur = x;
+    int64_t ld = ldx;
+    float* tmp = NULL;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int last = (l == n_layers - 1);
+        float* dst = last ? y : (float*)malloc(sizeof(float) * (size_t)B * widths[l + 1]);
+        const int64_t ldd = last ? ldy : widths[l + 1];
+        orc_fc(cur, ld, W[l], bias[l], B, widths[l], widths[l + 1], last ? final_act : hidden_act,
+               bf16_operands, dst, ldd);
+        free(tmp);
+        tmp = last ? NULL : dst;
+        cur = dst;
+        ld = ldd;
+    }
+}
+
+/* Pairwise-dot feature interaction (Section II-A, "Feature Interaction": the
+ * dense-stack output and the pooled embeddings are combined before the
+ * predictor stack).  vecs is [B][V][D]; slot 0 is the dense-stack output,
+ * slots 1..V-1 the pooled embeddings.  For each sample
+ *     out[b] = [ vecs[b][0][0..D) ,  <vecs[b][i], vecs[b][j]>  for i = 1..V-1, j = 0..i-1 ]
+ * i.e. the D values of slot 0 copied unchanged, then the strict lower triangle
+ * of V V^T in row-major order.  Width D + V(V-1)/2, row stride ldo. */
+void orc_interact(const float* vecs, int32_t B, int32_t V, int32_t D, float* out, int64_t ldo) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int32_t b = 0; b < B; ++b) {
+        const float* v = vecs + (int64_t)b * V * D;
+        float* o = out + b * ldo;
+        for (int32_t d = 0; d < D; ++d) o[d] = v[d];
+        int64_t p = D;
+        for (int32_t i = 1; i < V; ++i)
+            for (int32_t j = 0; j < i; ++j) {
+                double acc = 0.0;
+                for (int32_t d = 0; d < D; ++d) acc += (double)v[i * D + d] * (double)v[j * D + d];
+                o[p++] = (float)acc;
+            }
+    }
+}
+
+/* Whole model (Figure 2): offsets -> SLS into slots 1..T of [B][T+1][D];
+ * bottom stack (ReLU on every layer) into slot 0; interaction; top stack (ReLU
+ * on hidden layers, sigmoid on the 1-wide last layer) -> prob[B].
+ * Returns ORC_OK or the validator's status; nothing is computed on bad input. */
+int orc_model_forward(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                      const float* const* Wb, const float* const* bb, const int32_t* wb, int32_t nb,
+                      const float* const* Wt, const float* const* bt, const int32_t* wt, int32_t nt,
+                      int32_t bf16_operands, const float* dense, const int32_t* indices,
+                      int64_t n_indices, const int32_t* lengths, int32_t B, float* prob) {
+    if (wb[nb] != D || wt[0] != D + (T + 1) * T / 2 || wt[nt] != 1) return ORC_ERR_BAD_SHAPE;
+    int64_t n_bad, first_bad;
+    int st = orc_validate(rows, T, indices, n_indices, lengths, B, &n_bad, &first_bad);
+    if (st != ORC_OK) return st;
+    if (B == 0) return ORC_OK;
+    const int32_t V = T + 1;
+    int64_t* off = (int64_t*)malloc(sizeof(int64_t) * ((size_t)T * B + 1));
+    float* vecs = (float*)malloc(sizeof(float) * (size_t)B * V * D);
+    float* inter = (float*)malloc(sizeof(float) * (size_t)B * wt[0]);
+    orc_offsets(lengths, (int64_t)T * B, off);
+    orc_sls(tables, T, D, indices, off, B, vecs + D, (int64_t)V * D, D, NULL, NULL);
+    orc_mlp(Wb, bb, wb, nb, bf16_operands, ORC_ACT_RELU, ORC_ACT_RELU, dense, wb[0], vecs,
+            (int64_t)V * D, B);
+    orc_interact(vecs, B, V, D, inter, wt[0]);
+    orc_mlp(Wt, bt, wt, nt, bf16_operands, ORC_ACT_RELU, ORC_ACT_SIGMOID, inter, wt[0], prob, 1, B);
+    free(off);
+    free(vecs);
+    free(inter);
+    return ORC_OK;
+}
+
+/* Split a query of n items into consecutive sub-batches of size Bsz (Section
+ * IV-A: a query is divided into requests of a given batch size): floor(n/Bsz)
+ * full ones, then one of n mod Bsz if that is non-zero.  Writes (start, count)
+ * pairs and returns how many; pass NULL pointers to only count. */
+int64_t orc_split_query(int64_t n, int64_t Bsz, int64_t* start, int64_t* count) {
+    int64_t k = 0;
+    for (int64_t s = 0; s < n; s += Bsz, ++k) {
+        if (start) start[k] = s;
+        if (count) count[k] = (n - s < Bsz) ? n - s : Bsz;
+    }
+    return k;
+}

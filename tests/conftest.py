@@ -1,0 +1,30 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def read_golden(name):
+    """Parse tests/golden/<name>: '#' comments, 'key: v v v' lines, values as floats."""
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            k, v = line.split(":")
+            out[k.strip()] = [float(x) for x in v.split()]
+    return out
+
+
+@pytest.fixture
+def golden():
+    return read_golden

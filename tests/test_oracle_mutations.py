@@ -1,0 +1,50 @@
+"""Checks that the oracle's pins have teeth: each plausible mistake below is
+planted in a copy of the oracle source (on the CPU), and the pin tests must
+fail against that copy."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rec_oracle.c")
+
+MUTATIONS = {
+    "fc_transposed_weight": ("W[(int64_t)o * n_in + i]", "W[(int64_t)i * n_out + o]"),
+    "fc_dropped_bias": ("apply_act(acc + (double)bias[o], act)", "apply_act(acc, act)"),
+    "fc_bf16_ignored": ("if (bf16_operands) {", "if (0) {"),
+    "sigmoid_sign": ("1.0 / (1.0 + exp(-z))", "1.0 / (1.0 + exp(z))"),
+    "relu_dropped": ("z > 0.0 ? z : 0.0", "z"),
+    "sls_bag_order_sample_major": ("const int64_t bag = (int64_t)t * B + b;", "const int64_t bag = (int64_t)b * T + t;"),
+    "sls_drops_last_lookup": ("p < off[bag + 1]; ++p", "p < off[bag + 1] - 1; ++p"),
+    "sls_row_stride": ("(int64_t)indices[p] * D", "(int64_t)indices[p] * (D - 1)"),
+    "interact_upper_order": ("for (int32_t i = 1; i < V; ++i)\n            for (int32_t j = 0; j < i; ++j) {",
+                             "for (int32_t j = 0; j < V; ++j)\n            for (int32_t i = j + 1; i < V; ++i) {"),
+    "interact_includes_diagonal": ("for (int32_t j = 0; j < i; ++j) {", "for (int32_t j = 0; j <= i && p < D + V * (V - 1) / 2; ++j) {"),
+    "interact_slot0_not_copied": ("o[d] = v[d];", "o[d] = v[D + d];"),
+    "bf16_truncates": ("u += 0x7fffu + lsb;", "u += 0;"),
+    "validate_upper_bound_off_by_one": (">= rows[t])", "> rows[t])"),
+    "validate_ignores_negative": ("indices[pos] < 0 || ", ""),
+    "offsets_inclusive": ("off[i + 1] = off[i] + lengths[i];", "off[i + 1] = off[i] + lengths[i + 1 < n_bags ? i + 1 : i];"),
+    "model_top_uses_relu_last": ("ORC_ACT_RELU, ORC_ACT_SIGMOID, inter", "ORC_ACT_RELU, ORC_ACT_RELU, inter"),
+    "model_sls_into_slot0": ("vecs + D, (int64_t)V * D, D, NULL, NULL", "vecs, (int64_t)V * D, D, NULL, NULL"),
+    "split_drops_tail": ("(n - s < Bsz) ? n - s : Bsz", "Bsz"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_pins_catch_planted_mistake(name, tmp_path):
+    old, new = MUTATIONS[name]
+    src = open(SRC).read()
+    assert src.count(old) >= 1, f"mutation target not found: {old!r}"
+    mutated = tmp_path / "mut.c"
+    mutated.write_text(src.replace(old, new, 1))
+    lib = tmp_path / "libmut.so"
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-o", str(lib), str(mutated), "-lm"])
+    env = dict(os.environ, REC_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"pins did not notice mutation {name}"
+    assert "failed" in r.stdout
