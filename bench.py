@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched DLRM-style forward pass on one MI355X.
+
+A step is one rec_model_forward over one synthetic batch (offsets scan, fused
+SLS over all tables, bottom FC stack, pairwise-dot interaction, top FC stack +
+sigmoid), inputs already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload rmc2] [--sweep]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="rmc2", choices=["tiny", "rmc1", "rmc2", "rmc2-uniform", "rmc3"])
+    ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also replay 2000 lognormal-sized queries split into sub-batches of 16/64/256/1024")
+    return ap.parse_args()
+
+
+def sls_algorithmic_bytes(cfg, n_indices, B):
+    """Bytes the pooling must move if nothing is cached: per lookup one row (4D) and one
+    index (4); per bag one length (4) and one pooled row written (4D)."""
+    return n_indices * (4 * cfg.D + 4) + cfg.T * B * (4 + 4 * cfg.D)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def event_time(fn, steps, warmup, torch):
+    """Average device time per launch between two events on the launch stream."""
+    for i in range(warmup):
+        fn(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def cpu_baseline(cfg, batch):
+    """The oracle as it stands, timed on this host: whole forward of one full batch."""
+    import oracle
+    from paper_2001_02772_amd import synth
+    tables, idx = synth.compact_tables(cfg, batch)
+    pb, pt = synth.mlp_params(cfg.bottom, 0), synth.mlp_params(cfg.top, 1)
+
+    def oracle_forward(cfg, tables, batch, indices):
+        st, p = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, batch.dense, indices, batch.lengths,
+                                     bf16=cfg.bf16)
+        assert st == oracle.OK
+        return p
+
+    cores = min(16, os.cpu_count() or 1)
+    oracle.set_threads(cores)
+    oracle_forward(cfg, tables, batch, indices=idx)               # warm-up
+    best = 1e30
+    for _ in range(3):
+        t0 = time.perf_counter()
+        p_all = oracle_forward(cfg, tables, batch, indices=idx)
+        best = min(best, time.perf_counter() - t0)
+    oracle.set_threads(1)
+    t0 = time.perf_counter()
+    oracle_forward(cfg, tables, batch, indices=idx)
+    single = time.perf_counter() - t0
+    return {"value": batch.B / best, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": f"one full {cfg.name} batch of {batch.B} samples, whole forward, best of 3 on {cores} threads",
+            "single_thread_value": batch.B / single}, p_all
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the model is replicated and queries are split across GPUs with no communication).",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2001_02772_amd import rec, synth, workload
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    rec.lib()
+    cfg = synth.CONFIGS[a.workload]
+    t_setup = time.perf_counter()
+    model = workload.device_model(cfg)
+    gen = synth.BatchGenerator(cfg)
+    host_batches = [gen.batch(k) for k in range(a.batches)]
+    dbs = [workload.DeviceBatch(b) for b in host_batches]
+    probs = [torch.empty(cfg.B, dtype=torch.float32, device="cuda") for _ in dbs]
+    ws = model.workspace(cfg.B)
+    setup_s = time.perf_counter() - t_setup
+
+    def step(i):
+        d = dbs[i % len(dbs)]
+        model.forward(d.dense, d.indices, d.lengths, d.B, prob=probs[i % len(dbs)], workspace=ws)
+
+    sec = time_steps(step, a.steps, a.warmup, torch)
+    value = cfg.B / sec
+
+    # dominant kernel: the fused gather-and-pool, timed alone between events on its stream
+    offs = [rec.sls_offsets(d.lengths) for d in dbs]
+    V = cfg.T + 1
+    vecs = torch.empty((cfg.B, V, cfg.D), dtype=torch.float32, device="cuda")
+
+    def sls_only(i):
+        d = dbs[i % len(dbs)]
+        rec.sls_forward_offsets(model.tables, d.indices, offs[i % len(dbs)], d.B, out=vecs[:, 1:, :],
+                                out_stride_b=V * cfg.D, out_stride_t=cfg.D)
+
+    sls_sec = event_time(sls_only, a.steps, a.warmup, torch)
+    used = [dbs[i % len(dbs)].n_indices for i in range(a.steps)]
+    sls_bytes = float(np.mean([sls_algorithmic_bytes(cfg, n, cfg.B) for n in used]))
+    sls_gbs = sls_bytes / sls_sec / 1e9
+    roofline = {"bound": "hbm", "kernel": "sls_kernel", "achieved": sls_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": sls_gbs / HBM_PEAK_GBS, "traffic": None, "us_per_launch": sls_sec * 1e6,
+                "algorithmic_bytes_per_launch": sls_bytes}
+
+    # samples/s per sub-batch size (the batch sizes of the query-size sweep)
+    per_b = {}
+    for Bs in synth.SWEEP_BATCH_SIZES:
+        if Bs > cfg.B:
+            continue
+        subs = [workload.DeviceBatch(workload.slice_batch(host_batches[k % len(host_batches)], cfg.T, 0, Bs))
+                for k in range(4)]
+
+        def sub_step(i, subs=subs, Bs=Bs):
+            d = subs[i % len(subs)]
+            model.forward(d.dense, d.indices, d.lengths, Bs, prob=probs[0], workspace=ws)
+
+        s = time_steps(sub_step, max(50, a.steps // 2), 10, torch)
+        per_b[str(Bs)] = {"samples_per_s": Bs / s, "us_per_batch": s * 1e6}
+
+    out = {"metric": "samples/sec per batch size + SLS achieved HBM GB/s (RMC2-shaped, 1 GPU)",
+           "value": value, "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+           "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}-shaped DLRM forward", "batch": cfg.B, "tables": cfg.T, "rows": cfg.R,
+                      "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
+                      "bottom": list(cfg.bottom), "top": list(cfg.top), "distinct_batches": len(dbs)},
+           "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "setup_s": setup_s}
+
+    if a.sweep:
+        out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
+
+    if not a.no_cpu_baseline:
+        base, p_cpu = cpu_baseline(cfg, host_batches[0])
+        out["cpu_baseline"] = base
+        # the timed GPU path and the CPU baseline computed the same thing
+        step(0)
+        torch.cuda.synchronize()
+        p_gpu = probs[0].cpu().numpy()
+        out["max_abs_diff_vs_oracle"] = float(np.max(np.abs(p_gpu - p_cpu)))
+    print(json.dumps(out))
+
+
+def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np):
+    """2000 queries, sizes lognormal(4.5, 1.0) clipped to [1, 1000], each split into sub-batches
+    of B and served one after another; latency = first enqueue to completion of the last."""
+    sizes = synth.lognormal_query_sizes(synth.MASTER_SEED, synth.SWEEP_QUERIES)
+    pool = [gen.batch(100 + k, B=1000) for k in range(8)]           # item pools to cut queries from
+    res = {}
+    prob = torch.empty(1024, dtype=torch.float32, device="cuda")
+    for Bs in synth.SWEEP_BATCH_SIZES:
+        # pre-stage every sub-batch on the device (inputs resident, as for the headline number)
+        staged = []
+        for q, n in enumerate(sizes.tolist()):
+            src = pool[q % len(pool)]
+            staged.append([workload.DeviceBatch(workload.slice_batch(src, cfg.T, s, c))
+                           for s, c in rec.split_query(n, Bs)])
+        lat = np.empty(len(staged))
+        for warm in (True, False):
+            torch.cuda.synchronize()
+            t_all = time.perf_counter()
+            for q, subs in enumerate(staged):
+                t0 = time.perf_counter()
+                for d in subs:
+                    model.forward(d.dense, d.indices, d.lengths, d.B, prob=prob, workspace=ws)
+                torch.cuda.synchronize()
+                lat[q] = time.perf_counter() - t0
+                if warm and q >= 50:
+                    break
+            total = time.perf_counter() - t_all
+        srt = np.sort(lat)
+        rank = lambda p: float(srt[max(0, int(np.ceil(p * len(srt))) - 1)])
+        res[str(Bs)] = {"samples_per_s": float(sizes.sum() / total), "latency_ms_p50": rank(0.50) * 1e3,
+                        "latency_ms_p95": rank(0.95) * 1e3, "latency_ms_p99": rank(0.99) * 1e3}
+        del staged
+    return res
+
+
+if __name__ == "__main__":
+    main()

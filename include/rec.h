@@ -1,0 +1,189 @@
+/* rec.h -- C ABI of librec: batched forward inference of a DLRM-style
+ * recommendation model on one MI355X (gfx950).
+ *
+ * The model is the generalised architecture of Figure 2 / Section II-A of the
+ * DeepRecSys paper with the DLRM-RMC parameters of Table I: dense features go
+ * through a stack of fully-connected layers ("Dense-FC"), each sparse feature
+ * indexes rows of its embedding table and the rows are sum-pooled, the dense
+ * and pooled vectors are combined by a feature interaction, and a second FC
+ * stack ("Predict-FC") turns the result into one click-through probability per
+ * user-item pair.
+ *
+ * Conventions
+ *   - Pointers marked DEV are device pointers owned by the caller; pointers
+ *     marked HOST are host pointers read before the call returns.  The library
+ *     never allocates or frees device memory; scratch comes in through the
+ *     `workspace` arguments (256-byte aligned, at least *_workspace_bytes()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call except rec_sls_validate only enqueues work and returns.
+ *   - Errors that the host can see (null pointer, bad shape, small workspace)
+ *     are returned before anything is launched.  Errors that depend on device
+ *     data (negative length, lengths not summing to n_indices, index out of
+ *     range) are detected ONLY by rec_sls_validate; the forward calls do not
+ *     check device data and their behaviour on such input is undefined.
+ *   - Batch size 0 and empty bags are legal.
+ *   - Bags are table-major: bag t*B + b holds the lookups of sample b into
+ *     table t; `indices` is the concatenation of all bags in that order.
+ *   - Results are deterministic: no atomics, fixed reduction orders.
+ *   - Calls on different streams with disjoint workspaces and outputs may
+ *     overlap; a model handle is immutable after creation.
+ */
+#ifndef REC_H
+#define REC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    REC_OK = 0,
+    REC_ERR_NULL = 1,              /* a required pointer is NULL */
+    REC_ERR_BAD_SHAPE = 2,         /* negative / inconsistent sizes or strides */
+    REC_ERR_NEGATIVE_LENGTH = 3,   /* validate: some bag length < 0 */
+    REC_ERR_LENGTHS_MISMATCH = 4,  /* validate: sum(lengths) != n_indices */
+    REC_ERR_INDEX_RANGE = 5,       /* validate: some index outside [0, rows[t]) */
+    REC_ERR_WORKSPACE = 6,         /* workspace NULL, misaligned or too small */
+    REC_ERR_UNSUPPORTED = 7,       /* e.g. D not a multiple of 4, rows[t] > 2^31-1 */
+    REC_ERR_DEVICE = 8             /* a HIP call or kernel launch failed */
+} rec_status;
+
+typedef enum { REC_F32 = 0, REC_BF16 = 1 } rec_dtype;
+typedef enum { REC_ACT_NONE = 0, REC_ACT_RELU = 1, REC_ACT_SIGMOID = 2 } rec_act;
+
+/* Static, NUL-terminated name of a status code. */
+const char* rec_status_string(rec_status s);
+
+/* ---- query splitting (Section IV-A: a query of n candidate items is divided
+ * into requests of a chosen batch size) ------------------------------------
+ * Consecutive slices: floor(n/batch) of size `batch`, then one of n mod batch
+ * if that is non-zero.  Writes (start, count) pairs to the HOST arrays and
+ * returns the number of slices; with start == count == NULL it only counts.
+ * Returns -1 if n < 0 or batch < 1. */
+int64_t rec_split_query(int64_t n, int64_t batch, int64_t* start, int64_t* count);
+
+/* ---- embedding lookup + sum pooling (Section II-A, "Embedding Table Access";
+ * Table I, pooling = Sum) ----------------------------------------------------
+ *   E[b][t][:] = sum_{k < lengths[t*B+b]} Table_t[ indices[off(t,b) + k] ][:]
+ * for all T tables in one launch; duplicates count with multiplicity, an
+ * empty bag gives zeros.  Sums are fp32.
+ *
+ *   tables      DEV array of T DEV pointers, table t is fp32 [rows[t]][D]
+ *               row-major, base 16-byte aligned (256-byte recommended)
+ *   rows        HOST int64[T], each in [1, 2^31-1]
+ *   D           multiple of 4, 4 <= D <= 256
+ *   indices     DEV int32 [n_indices]
+ *   lengths     DEV int32 [T*B]
+ *   out         DEV fp32; element (b,t,d) at out[b*out_stride_b + t*out_stride_t + d]
+ *               (strides in floats, multiples of 4, out 16-byte aligned), so the
+ *               result can land in slots 1..T of a [B][T+1][D] interaction buffer
+ *   workspace   DEV, >= rec_sls_workspace_bytes(T, B); receives the offsets
+ */
+size_t rec_sls_workspace_bytes(int32_t T, int32_t B);
+rec_status rec_sls_forward(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                           const int32_t* indices, int64_t n_indices, const int32_t* lengths,
+                           int32_t B, float* out, int64_t out_stride_b, int64_t out_stride_t,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same pooling with the bag offsets already computed (rec_sls_offsets):
+ * offsets DEV int64 [T*B + 1], bag i covers indices[offsets[i] .. offsets[i+1]).
+ * Launches the gather-and-pool kernel alone; needs no workspace. */
+rec_status rec_sls_forward_offsets(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                                   const int32_t* indices, int64_t n_indices, const int64_t* offsets,
+                                   int32_t B, float* out, int64_t out_stride_b, int64_t out_stride_t,
+                                   void* stream);
+
+/* Exclusive prefix sum of bag lengths (the offsets used above):
+ * offsets[0] = 0, offsets[i+1] = offsets[i] + lengths[i].
+ * lengths DEV int32 [n_bags]; offsets DEV int64 [n_bags + 1], 16-byte aligned. */
+rec_status rec_sls_offsets(const int32_t* lengths, int64_t n_bags, int64_t* offsets, void* stream);
+
+/* Input check for the sparse side; SYNCHRONOUS (waits for `stream`, reads a
+ * few words back).  In this order: any length < 0 -> REC_ERR_NEGATIVE_LENGTH;
+ * 64-bit sum of lengths != n_indices -> REC_ERR_LENGTHS_MISMATCH; any index of
+ * table t outside [0, rows[t]) -> REC_ERR_INDEX_RANGE with *n_bad = how many
+ * and *first_bad = flat position of the first (else 0 and -1).
+ * n_bad / first_bad are HOST pointers (may be NULL).  Same workspace size as
+ * rec_sls_forward. */
+rec_status rec_sls_validate(const int64_t* rows, int32_t T, const int32_t* indices,
+                            int64_t n_indices, const int32_t* lengths, int32_t B,
+                            int64_t* n_bad, int64_t* first_bad,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- fully-connected stacks (Section II-A, "Features" and "Product
+ * Ranking"; widths per Table I) -----------------------------------------------
+ *   y = act_L( ... act_1( x W_1^T + b_1 ) ... W_L^T + b_L )
+ * Hidden layers use hidden_act, the last layer final_act.
+ *
+ *   W        HOST array of n_layers DEV pointers; W[l] is [widths[l+1]][widths[l]]
+ *            row-major in `wdtype` (REC_F32: float; REC_BF16: bfloat16 bit patterns)
+ *   bias     HOST array of n_layers DEV pointers to fp32 [widths[l+1]]
+ *   widths   HOST int32 [n_layers + 1], all >= 1
+ *   x        DEV fp32 [B][widths[0]], row stride ldx floats
+ *   y        DEV fp32 [B][widths[n_layers]], row stride ldy floats
+ * REC_F32: fp32 operands, fp32 accumulation.  REC_BF16: the activations entering
+ * each layer and the weights are bf16 (round to nearest even), products are
+ * accumulated in fp32, bias and activation are applied in fp32, y is fp32. */
+size_t rec_mlp_workspace_bytes(const int32_t* widths, int32_t n_layers, int32_t B, rec_dtype wdtype);
+rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const int32_t* widths,
+                           int32_t n_layers, rec_dtype wdtype, rec_act hidden_act, rec_act final_act,
+                           const float* x, int64_t ldx, float* y, int64_t ldy, int32_t B,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* fp32 -> bfloat16 (round to nearest even, NaN stays NaN), for preparing
+ * REC_BF16 weights.  src DEV fp32 [n], dst DEV uint16 [n]. */
+rec_status rec_f32_to_bf16(const float* src, uint16_t* dst, int64_t n, void* stream);
+
+/* ---- feature interaction (Section II-A, "Feature Interaction": the outputs of
+ * the dense and sparse sides are combined before the predictor stack) ---------
+ * Pairwise dot products: vecs DEV fp32 [B][V][D] (slot 0 = dense-stack output,
+ * slots 1..V-1 = pooled embeddings), and for each sample
+ *   out[b] = [ vecs[b][0][0..D) , <vecs[b][i], vecs[b][j]> for i = 1..V-1, j = 0..i-1 ]
+ * i.e. slot 0 copied, then the strict lower triangle of V V^T row by row.
+ * out DEV fp32 [B][D + V(V-1)/2], row stride ldo floats.  1 <= V <= 128,
+ * D multiple of 4, 4 <= D <= 256. */
+rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int32_t D,
+                        float* out, int64_t ldo, void* stream);
+
+/* ---- whole model (Figure 2) ------------------------------------------------
+ * offsets -> SLS into slots 1..T of [B][T+1][D]; bottom stack (ReLU after every
+ * layer) into slot 0; interaction; top stack (ReLU on hidden layers, sigmoid on
+ * the 1-wide last layer) -> one probability per sample.
+ * The handle BORROWS every pointer in the descriptor: DEV memory must stay
+ * alive and unchanged while the handle is used; HOST arrays are copied. */
+typedef struct {
+    int32_t T;                       /* embedding tables, 1 <= T <= 127 */
+    int32_t D;                       /* embedding dim = bottom stack output width */
+    const float* const* tables;      /* DEV array of T DEV pointers (as rec_sls_forward) */
+    const int64_t* rows;             /* HOST int64[T] */
+    int32_t n_bottom;                /* bottom layers */
+    const int32_t* bottom_widths;    /* HOST [n_bottom+1]; [0] = dense features F, last = D */
+    const void* const* bottom_W;     /* HOST array of DEV pointers (as rec_mlp_forward) */
+    const float* const* bottom_b;
+    int32_t n_top;                   /* top layers */
+    const int32_t* top_widths;       /* HOST [n_top+1]; [0] = D + T(T+1)/2, last = 1 */
+    const void* const* top_W;
+    const float* const* top_b;
+    rec_dtype mlp_dtype;             /* REC_F32 or REC_BF16, both stacks */
+} rec_model_desc;
+
+typedef struct rec_model rec_model;
+
+rec_status rec_model_create(const rec_model_desc* desc, rec_model** out);
+void rec_model_destroy(rec_model* m);
+size_t rec_model_workspace_bytes(const rec_model* m, int32_t B_max);
+
+/*   dense    DEV fp32 [B][F] contiguous
+ *   indices  DEV int32 [n_indices];  lengths DEV int32 [T*B]
+ *   prob     DEV fp32 [B]
+ *   workspace >= rec_model_workspace_bytes(m, B) */
+rec_status rec_model_forward(const rec_model* m, const float* dense, const int32_t* indices,
+                             int64_t n_indices, const int32_t* lengths, int32_t B, float* prob,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REC_H */

@@ -1,0 +1,159 @@
+// Whole-model forward (Figure 2 of the DeepRecSys paper): embedding bags and the
+// dense stack feed the interaction, the predictor stack ends in a sigmoid.
+// Also the host-side query splitter of Section IV-A and the status names.
+#include <new>
+#include <vector>
+
+#include "rec_common.h"
+
+struct rec_model {
+    int32_t T, D;
+    const float* const* tables;
+    std::vector<int64_t> rows;
+    std::vector<int32_t> bottom_widths, top_widths;
+    std::vector<const void*> bottom_W, top_W;
+    std::vector<const float*> bottom_b, top_b;
+    rec_dtype dt;
+    int64_t ld_inter;        // row stride of the interaction output
+};
+
+namespace {
+
+struct ModelWorkspace {
+    void* sls;
+    size_t sls_bytes;
+    float* vecs;
+    float* inter;
+    void* mlp;
+    size_t mlp_bytes;
+    size_t total;
+};
+
+ModelWorkspace carve(const rec_model* m, int32_t B, void* base) {
+    ModelWorkspace w;
+    char* p = static_cast<char*>(base);
+    const int32_t V = m->T + 1;
+    w.sls = p;
+    w.sls_bytes = rec_sls_workspace_bytes(m->T, B);
+    p += w.sls_bytes;
+    w.vecs = reinterpret_cast<float*>(p);
+    p += rec_round_up((size_t)B * V * m->D * sizeof(float), 256);
+    w.inter = reinterpret_cast<float*>(p);
+    p += rec_round_up((size_t)B * m->ld_inter * sizeof(float), 256);
+    w.mlp = p;
+    const size_t a = rec_mlp_workspace_bytes(m->bottom_widths.data(), (int32_t)m->bottom_W.size(), B, m->dt);
+    const size_t c = rec_mlp_workspace_bytes(m->top_widths.data(), (int32_t)m->top_W.size(), B, m->dt);
+    w.mlp_bytes = a > c ? a : c;
+    p += w.mlp_bytes;
+    w.total = (size_t)(p - static_cast<char*>(base));
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rec_status_string(rec_status s) {
+    switch (s) {
+        case REC_OK: return "REC_OK";
+        case REC_ERR_NULL: return "REC_ERR_NULL";
+        case REC_ERR_BAD_SHAPE: return "REC_ERR_BAD_SHAPE";
+        case REC_ERR_NEGATIVE_LENGTH: return "REC_ERR_NEGATIVE_LENGTH";
+        case REC_ERR_LENGTHS_MISMATCH: return "REC_ERR_LENGTHS_MISMATCH";
+        case REC_ERR_INDEX_RANGE: return "REC_ERR_INDEX_RANGE";
+        case REC_ERR_WORKSPACE: return "REC_ERR_WORKSPACE";
+        case REC_ERR_UNSUPPORTED: return "REC_ERR_UNSUPPORTED";
+        case REC_ERR_DEVICE: return "REC_ERR_DEVICE";
+    }
+    return "REC_ERR_UNKNOWN";
+}
+
+int64_t rec_split_query(int64_t n, int64_t batch, int64_t* start, int64_t* count) {
+    if (n < 0 || batch < 1) return -1;
+    const int64_t full = n / batch, rem = n % batch;
+    for (int64_t k = 0; k < full; ++k) {
+        if (start) start[k] = k * batch;
+        if (count) count[k] = batch;
+    }
+    if (rem) {
+        if (start) start[full] = full * batch;
+        if (count) count[full] = rem;
+    }
+    return full + (rem ? 1 : 0);
+}
+
+rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
+    if (!d || !out) return REC_ERR_NULL;
+    *out = nullptr;
+    if (!d->tables || !d->rows || !d->bottom_widths || !d->bottom_W || !d->bottom_b || !d->top_widths || !d->top_W ||
+        !d->top_b)
+        return REC_ERR_NULL;
+    if (d->T < 1 || d->n_bottom < 1 || d->n_top < 1) return REC_ERR_BAD_SHAPE;
+    if (d->T > 127 || d->D < 4 || d->D > 256 || d->D % 4) return REC_ERR_UNSUPPORTED;
+    if (d->mlp_dtype != REC_F32 && d->mlp_dtype != REC_BF16) return REC_ERR_UNSUPPORTED;
+    for (int32_t l = 0; l <= d->n_bottom; ++l)
+        if (d->bottom_widths[l] < 1) return REC_ERR_BAD_SHAPE;
+    for (int32_t l = 0; l <= d->n_top; ++l)
+        if (d->top_widths[l] < 1) return REC_ERR_BAD_SHAPE;
+    const int32_t V = d->T + 1;
+    if (d->bottom_widths[d->n_bottom] != d->D) return REC_ERR_BAD_SHAPE;
+    if (d->top_widths[0] != d->D + V * (V - 1) / 2 || d->top_widths[d->n_top] != 1) return REC_ERR_BAD_SHAPE;
+    for (int32_t t = 0; t < d->T; ++t) {
+        if (d->rows[t] < 1) return REC_ERR_BAD_SHAPE;
+        if (d->rows[t] > 2147483647LL) return REC_ERR_UNSUPPORTED;
+    }
+    for (int32_t l = 0; l < d->n_bottom; ++l)
+        if (!d->bottom_W[l] || !d->bottom_b[l]) return REC_ERR_NULL;
+    for (int32_t l = 0; l < d->n_top; ++l)
+        if (!d->top_W[l] || !d->top_b[l]) return REC_ERR_NULL;
+    rec_model* m = new (std::nothrow) rec_model;
+    if (!m) return REC_ERR_DEVICE;
+    m->T = d->T;
+    m->D = d->D;
+    m->tables = d->tables;
+    m->rows.assign(d->rows, d->rows + d->T);
+    m->bottom_widths.assign(d->bottom_widths, d->bottom_widths + d->n_bottom + 1);
+    m->top_widths.assign(d->top_widths, d->top_widths + d->n_top + 1);
+    m->bottom_W.assign(d->bottom_W, d->bottom_W + d->n_bottom);
+    m->bottom_b.assign(d->bottom_b, d->bottom_b + d->n_bottom);
+    m->top_W.assign(d->top_W, d->top_W + d->n_top);
+    m->top_b.assign(d->top_b, d->top_b + d->n_top);
+    m->dt = d->mlp_dtype;
+    m->ld_inter = (d->top_widths[0] + 3) / 4 * 4;
+    *out = m;
+    return REC_OK;
+}
+
+void rec_model_destroy(rec_model* m) { delete m; }
+
+size_t rec_model_workspace_bytes(const rec_model* m, int32_t B_max) {
+    if (!m || B_max < 0) return 0;
+    return carve(m, B_max, nullptr).total;
+}
+
+rec_status rec_model_forward(const rec_model* m, const float* dense, const int32_t* indices, int64_t n_indices,
+                             const int32_t* lengths, int32_t B, float* prob, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!m) return REC_ERR_NULL;
+    if (B < 0 || n_indices < 0) return REC_ERR_BAD_SHAPE;
+    if (B == 0) return REC_OK;
+    if (!dense || !lengths || !prob || (n_indices > 0 && !indices)) return REC_ERR_NULL;
+    if (!workspace || !rec_aligned(workspace, 256)) return REC_ERR_WORKSPACE;
+    const ModelWorkspace w = carve(m, B, workspace);
+    if (workspace_bytes < w.total) return REC_ERR_WORKSPACE;
+    const int32_t V = m->T + 1, D = m->D;
+
+    rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
+                                    (int64_t)V * D, D, w.sls, w.sls_bytes, stream);
+    if (st != REC_OK) return st;
+    st = rec_mlp_forward(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(), (int32_t)m->bottom_W.size(),
+                         m->dt, REC_ACT_RELU, REC_ACT_RELU, dense, m->bottom_widths[0], w.vecs, (int64_t)V * D, B, w.mlp,
+                         w.mlp_bytes, stream);
+    if (st != REC_OK) return st;
+    st = rec_interact(w.vecs, B, V, D, w.inter, m->ld_inter, stream);
+    if (st != REC_OK) return st;
+    return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths.data(), (int32_t)m->top_W.size(), m->dt,
+                           REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, m->ld_inter, prob, 1, B, w.mlp, w.mlp_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,31 @@
+// Internal helpers shared by the librec translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rec.h"
+
+#define REC_WAVE 64
+
+#define REC_CHECK_LAUNCH()                                   \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return REC_ERR_DEVICE; \
+    } while (0)
+
+static inline bool rec_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+static inline size_t rec_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// fp32 -> bf16 bit pattern, round to nearest even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint16_t rec_f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float rec_apply_act(float z, int act) {
+    if (act == REC_ACT_RELU) return z > 0.0f ? z : 0.0f;
+    if (act == REC_ACT_SIGMOID) return 1.0f / (1.0f + expf(-z));
+    return z;
+}

@@ -1,0 +1,302 @@
+"""Thin binding of librec's C ABI (see include/rec.h): argument marshalling only.
+
+Every step of the model runs in the library's HIP kernels.  PyTorch is used for
+device memory (``torch.empty(..., device="cuda")``) and for the current stream,
+nothing else.  There is no CPU fallback: a missing library or a non-zero status
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+LIB_PATH = os.path.join(_HERE, "librec.so")
+SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("sls.hip", "fc.hip", "interact.hip", "model.hip")]
+
+OK, ERR_NULL, ERR_BAD_SHAPE, ERR_NEGATIVE_LENGTH, ERR_LENGTHS_MISMATCH, ERR_INDEX_RANGE, \
+    ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(9)
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_SIGMOID = 0, 1, 2
+
+EXPORTS = (
+    "rec_status_string", "rec_split_query",
+    "rec_sls_workspace_bytes", "rec_sls_forward", "rec_sls_forward_offsets", "rec_sls_offsets", "rec_sls_validate",
+    "rec_mlp_workspace_bytes", "rec_mlp_forward", "rec_f32_to_bf16",
+    "rec_interact",
+    "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
+)
+
+
+class RecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile the HIP sources for gfx950 into librec.so next to this file."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-I" + os.path.join(_ROOT, "include"),
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", LIB_PATH] + SOURCES
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    """Load librec.so (building it only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        build_library()
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.rec_status_string.restype = C.c_char_p
+    L.rec_status_string.argtypes = [C.c_int]
+    L.rec_split_query.restype = i64
+    L.rec_split_query.argtypes = [i64, i64, vp, vp]
+    L.rec_sls_workspace_bytes.restype = sz
+    L.rec_sls_workspace_bytes.argtypes = [i32, i32]
+    L.rec_sls_forward.restype = C.c_int
+    L.rec_sls_forward.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, i64, i64, vp, sz, vp]
+    L.rec_sls_forward_offsets.restype = C.c_int
+    L.rec_sls_forward_offsets.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, i64, i64, vp]
+    L.rec_sls_offsets.restype = C.c_int
+    L.rec_sls_offsets.argtypes = [vp, i64, vp, vp]
+    L.rec_sls_validate.restype = C.c_int
+    L.rec_sls_validate.argtypes = [vp, i32, vp, i64, vp, i32, vp, vp, vp, sz, vp]
+    L.rec_mlp_workspace_bytes.restype = sz
+    L.rec_mlp_workspace_bytes.argtypes = [vp, i32, i32, C.c_int]
+    L.rec_mlp_forward.restype = C.c_int
+    L.rec_mlp_forward.argtypes = [vp, vp, vp, i32, C.c_int, C.c_int, C.c_int, vp, i64, vp, i64, i32, vp, sz, vp]
+    L.rec_f32_to_bf16.restype = C.c_int
+    L.rec_f32_to_bf16.argtypes = [vp, vp, i64, vp]
+    L.rec_interact.restype = C.c_int
+    L.rec_interact.argtypes = [vp, i32, i32, i32, vp, i64, vp]
+    L.rec_model_create.restype = C.c_int
+    L.rec_model_create.argtypes = [vp, vp]
+    L.rec_model_destroy.restype = None
+    L.rec_model_destroy.argtypes = [vp]
+    L.rec_model_workspace_bytes.restype = sz
+    L.rec_model_workspace_bytes.argtypes = [vp, i32]
+    L.rec_model_forward.restype = C.c_int
+    L.rec_model_forward.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().rec_status_string(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise RecError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _host_i32(v):
+    return np.ascontiguousarray(v, dtype=np.int32)
+
+
+def _host_i64(v):
+    return np.ascontiguousarray(v, dtype=np.int64)
+
+
+def _ptr_array_host(tensors):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def split_query(n: int, batch: int):
+    k = lib().rec_split_query(n, batch, None, None)
+    if k < 0:
+        raise RecError(ERR_BAD_SHAPE, "rec_split_query")
+    start, count = np.empty(k, np.int64), np.empty(k, np.int64)
+    lib().rec_split_query(n, batch, start.ctypes.data, count.ctypes.data)
+    return list(zip(start.tolist(), count.tolist()))
+
+
+class Tables:
+    """T embedding tables on the device plus the device array of their base pointers."""
+
+    def __init__(self, tables):
+        self.tensors = list(tables)
+        for t in self.tensors:
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.dim() == 2
+        self.T = len(self.tensors)
+        self.D = self.tensors[0].shape[1]
+        self.rows = _host_i64([t.shape[0] for t in self.tensors])
+        self.ptrs = torch.tensor([t.data_ptr() for t in self.tensors], dtype=torch.int64,
+                                 device=self.tensors[0].device)
+
+
+def sls_workspace_bytes(T: int, B: int) -> int:
+    return lib().rec_sls_workspace_bytes(T, B)
+
+
+def sls_forward(tables: Tables, indices, lengths, B: int, out=None, out_stride_b=None, out_stride_t=None,
+                workspace=None):
+    """E[b][t][:] = sum of the looked-up rows; returns fp32 [B][T][D] unless `out` is given."""
+    T, D = tables.T, tables.D
+    dev = tables.ptrs.device
+    if out is None:
+        out = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+        out_stride_b, out_stride_t = T * D, D
+    if workspace is None:
+        workspace = _workspace(sls_workspace_bytes(T, B), dev)
+    st = lib().rec_sls_forward(_ptr(tables.ptrs), tables.rows.ctypes.data, T, D, _ptr(indices), indices.numel(),
+                               _ptr(lengths), B, _ptr(out), out_stride_b, out_stride_t, _ptr(workspace),
+                               workspace.numel(), _stream())
+    _check(st, "rec_sls_forward")
+    return out
+
+
+def sls_forward_offsets(tables: Tables, indices, offsets, B: int, out=None, out_stride_b=None, out_stride_t=None):
+    """Pooling kernel alone, from precomputed int64 bag offsets."""
+    T, D = tables.T, tables.D
+    if out is None:
+        out = torch.empty((B, T, D), dtype=torch.float32, device=tables.ptrs.device)
+        out_stride_b, out_stride_t = T * D, D
+    st = lib().rec_sls_forward_offsets(_ptr(tables.ptrs), tables.rows.ctypes.data, T, D, _ptr(indices),
+                                       indices.numel(), _ptr(offsets), B, _ptr(out), out_stride_b, out_stride_t,
+                                       _stream())
+    _check(st, "rec_sls_forward_offsets")
+    return out
+
+
+def sls_offsets(lengths):
+    n = lengths.numel()
+    off = torch.empty(n + 1, dtype=torch.int64, device=lengths.device)
+    _check(lib().rec_sls_offsets(_ptr(lengths), n, _ptr(off), _stream()), "rec_sls_offsets")
+    return off
+
+
+def sls_validate(rows, indices, lengths, B: int, workspace=None):
+    """Returns (status, n_bad, first_bad); does not raise on data errors."""
+    rows = _host_i64(rows)
+    T = len(rows)
+    if workspace is None:
+        workspace = _workspace(sls_workspace_bytes(T, B), lengths.device)
+    n_bad, first_bad = C.c_int64(0), C.c_int64(-1)
+    st = lib().rec_sls_validate(rows.ctypes.data, T, _ptr(indices), indices.numel(), _ptr(lengths), B,
+                                C.addressof(n_bad), C.addressof(first_bad), _ptr(workspace), workspace.numel(),
+                                _stream())
+    return st, n_bad.value, first_bad.value
+
+
+def f32_to_bf16(src):
+    """fp32 device tensor -> int16 tensor of bfloat16 bit patterns (round to nearest even)."""
+    dst = torch.empty(src.shape, dtype=torch.int16, device=src.device)
+    _check(lib().rec_f32_to_bf16(_ptr(src), _ptr(dst), src.numel(), _stream()), "rec_f32_to_bf16")
+    return dst
+
+
+def mlp_workspace_bytes(widths, B: int, wdtype: int) -> int:
+    w = _host_i32(widths)
+    return lib().rec_mlp_workspace_bytes(w.ctypes.data, len(w) - 1, B, wdtype)
+
+
+def mlp_forward(W, bias, x, hidden_act=ACT_RELU, final_act=ACT_RELU, wdtype=F32, y=None, ldy=None, workspace=None):
+    """W: list of device tensors [out][in] (fp32, or int16 bf16 patterns for BF16); x fp32 [B][in]."""
+    widths = _host_i32([W[0].shape[1]] + [w.shape[0] for w in W])
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, int(widths[-1])), dtype=torch.float32, device=x.device)
+        ldy = int(widths[-1])
+    if workspace is None:
+        workspace = _workspace(mlp_workspace_bytes(widths, B, wdtype), x.device)
+    Wp, bp = _ptr_array_host(W), _ptr_array_host(bias)
+    st = lib().rec_mlp_forward(C.addressof(Wp), C.addressof(bp), widths.ctypes.data, len(W), wdtype, hidden_act,
+                               final_act, _ptr(x), x.stride(0) if B else int(widths[0]), _ptr(y), ldy, B,
+                               _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "rec_mlp_forward")
+    return y
+
+
+def interact(vecs, out=None, ldo=None):
+    B, V, D = vecs.shape
+    if out is None:
+        ldo = D + V * (V - 1) // 2
+        out = torch.empty((B, ldo), dtype=torch.float32, device=vecs.device)
+    _check(lib().rec_interact(_ptr(vecs), B, V, D, _ptr(out), ldo, _stream()), "rec_interact")
+    return out
+
+
+class _ModelDesc(C.Structure):
+    _fields_ = [("T", C.c_int32), ("D", C.c_int32), ("tables", C.c_void_p), ("rows", C.c_void_p),
+                ("n_bottom", C.c_int32), ("bottom_widths", C.c_void_p), ("bottom_W", C.c_void_p),
+                ("bottom_b", C.c_void_p),
+                ("n_top", C.c_int32), ("top_widths", C.c_void_p), ("top_W", C.c_void_p), ("top_b", C.c_void_p),
+                ("mlp_dtype", C.c_int)]
+
+
+class Model:
+    """Owns the device tensors of one model and the library handle that borrows them."""
+
+    def __init__(self, tables: Tables, bottom_W, bottom_b, top_W, top_b, wdtype=F32):
+        self.tables, self.wdtype = tables, wdtype
+        self.bottom_W, self.bottom_b, self.top_W, self.top_b = list(bottom_W), list(bottom_b), list(top_W), list(top_b)
+        self.bottom_widths = _host_i32([bottom_W[0].shape[1]] + [w.shape[0] for w in bottom_W])
+        self.top_widths = _host_i32([top_W[0].shape[1]] + [w.shape[0] for w in top_W])
+        self.device = tables.ptrs.device
+        arrays = [_ptr_array_host(a) for a in (self.bottom_W, self.bottom_b, self.top_W, self.top_b)]
+        d = _ModelDesc(tables.T, tables.D, _ptr(tables.ptrs), tables.rows.ctypes.data,
+                       len(self.bottom_W), self.bottom_widths.ctypes.data, C.addressof(arrays[0]), C.addressof(arrays[1]),
+                       len(self.top_W), self.top_widths.ctypes.data, C.addressof(arrays[2]), C.addressof(arrays[3]),
+                       wdtype)
+        h = C.c_void_p(0)
+        _check(lib().rec_model_create(C.addressof(d), C.addressof(h)), "rec_model_create")
+        self._h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().rec_model_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def workspace_bytes(self, B: int) -> int:
+        return lib().rec_model_workspace_bytes(self._h, B)
+
+    def workspace(self, B: int) -> torch.Tensor:
+        need = self.workspace_bytes(B)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = _workspace(need, self.device)
+        return self._ws
+
+    def forward(self, dense, indices, lengths, B: int, prob=None, workspace=None):
+        if prob is None:
+            prob = torch.empty(B, dtype=torch.float32, device=self.device)
+        if workspace is None:
+            workspace = self.workspace(B)
+        st = lib().rec_model_forward(self._h, _ptr(dense), _ptr(indices), indices.numel(), _ptr(lengths), B,
+                                     _ptr(prob), _ptr(workspace), workspace.numel(), _stream())
+        _check(st, "rec_model_forward")
+        return prob

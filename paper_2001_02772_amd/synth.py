@@ -317,3 +317,19 @@ class BatchGenerator:
                 parts.append(randint(self.seed, st, base, n, 0, cfg.R - 1))
         indices = np.concatenate(parts) if parts else np.zeros(0, np.int64)
         return Batch(B, dense, lengths.astype(np.int32), indices.astype(np.int32))
+
+
+def compact_tables(cfg: Config, batch: Batch, seed: int = MASTER_SEED):
+    """Only the table rows a batch touches, as small per-table arrays, plus the batch's
+    indices renumbered into them.  Lets a CPU run of a full-size batch do without the
+    multi-GB tables: pooled sums over the compact tables equal those over the full ones."""
+    off = np.concatenate([[0], np.cumsum(batch.lengths, dtype=np.int64)])
+    tables, idx = [], np.empty_like(batch.indices)
+    for t in range(cfg.T):
+        lo, hi = off[t * batch.B], off[(t + 1) * batch.B]
+        used = np.unique(batch.indices[lo:hi])
+        if used.size == 0:
+            used = np.zeros(1, dtype=batch.indices.dtype)
+        tables.append(table_rows(cfg, t, used, seed))
+        idx[lo:hi] = np.searchsorted(used, batch.indices[lo:hi])
+    return tables, idx
