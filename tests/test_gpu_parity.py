@@ -80,9 +80,9 @@ def test_validate_matches_oracle(rec):
 
 
 def test_bf16_conversion_bit_exact(rec):
-    x = np.concatenate([rng.normal(size=100_000).astype(np.float32) * 10.0 ** rng.integers(-8, 8, size=100_000),
-                        np.array([0.0, -0.0, 1.0, 1 + 2.0**-8, 1 + 3 * 2.0**-8, np.inf, -np.inf, 3.4e38, 1e-40, np.nan],
-                                 np.float32)])
+    x = np.concatenate([rng.normal(size=100_000) * 10.0 ** rng.integers(-8, 8, size=100_000),
+                        np.array([0.0, -0.0, 1.0, 1 + 2.0**-8, 1 + 3 * 2.0**-8, np.inf, -np.inf, 3.4e38, 1e-40, np.nan])]
+                       ).astype(np.float32)
     got = rec.f32_to_bf16(dev(x)).cpu().numpy().view(np.uint16)
     want = (oracle.bf16_round(x).view(np.uint32) >> 16).astype(np.uint16)
     assert np.array_equal(got, want)
