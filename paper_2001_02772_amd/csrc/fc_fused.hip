@@ -1,0 +1,399 @@
+// Several narrow FC layers in one launch.
+//
+// The Dense-FC and Predict-FC stacks of Table I (DeepRecSys paper, Section II-A)
+// end in -- or consist of -- layers a few hundred units wide.  At a batch of a
+// thousand rows each such layer is a few microseconds of matrix-core work, so a
+// launch per layer is mostly launch latency and a round trip of the activations
+// through memory.  Here a block takes 16 samples through up to four consecutive
+// layers: activations stay in LDS (two ping-pong buffers), the weights of each
+// layer stream from L2 straight into MFMA operand registers (every block reads
+// them once), and only the last layer's output goes back to memory.
+// fp32: v_mfma_f32_16x16x4_f32;  bf16 operands: v_mfma_f32_16x16x32_bf16.
+#include "rec_common.h"
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
+
+constexpr int FM_ROWS = 16;
+constexpr int FM_WAVES = 16;
+constexpr int FM_THREADS = FM_WAVES * 64;
+
+template <bool BF16>
+struct FM {
+    static constexpr int MAXW = BF16 ? REC_FUSED_MAX_WIDTH_BF16 : REC_FUSED_MAX_WIDTH_F32;
+    static constexpr int ELT = BF16 ? 2 : 4;
+    static constexpr int KCH = BF16 ? 32 : 16;                 // k covered by one operand load per lane
+    static constexpr int LDA = MAXW + 16 / ELT;                // padded activation row (elements)
+    static constexpr int BUF_BYTES = FM_ROWS * LDA * ELT;
+    typedef typename std::conditional<BF16, uint16_t, float>::type act_t;
+};
+
+template <bool BF16>
+__device__ __forceinline__ typename FM<BF16>::act_t to_act(float v) {
+    if constexpr (BF16) return rec_f32_to_bf16_bits(v);
+    else return v;
+}
+
+// One pipeline item: the weights a lane needs for GU consecutive k-chunks of one 16-column tile.
+template <bool BF16>
+struct WGroup {
+    static constexpr int GU = 8;
+    typedef typename std::conditional<BF16, ushort8, float4>::type reg_t;
+    reg_t w[GU];
+};
+
+// Raw loads of one item: lane (li, q) fetches, for each of the GU chunks, the VEC consecutive k
+// of weight row n0+li that it will feed to the MFMAs.  Out-of-range lanes read a valid (clamped)
+// address and the value is discarded by mask_group() when the item is consumed.  Nothing here
+// uses a loaded value, so the loads stay in flight while the previous item is multiplied.
+template <bool BF16>
+__device__ __forceinline__ void load_group(WGroup<BF16>& g, const void* Wv, int K, int N, int n0, int k0, int li, int q) {
+    constexpr int KCH = FM<BF16>::KCH;
+    constexpr int VEC = BF16 ? 8 : 4;
+    typedef typename std::conditional<BF16, uint16_t, float>::type w_t;
+    typedef typename WGroup<BF16>::reg_t reg_t;
+    const w_t* __restrict__ W = static_cast<const w_t*>(Wv);
+    const bool vec = (K % VEC == 0) && rec_dev_aligned(W, 16);
+    const int n = n0 + li;
+    const w_t* wrow = W + (int64_t)(n < N ? n : 0) * K;
+    if (vec) {
+#pragma unroll
+        for (int u = 0; u < WGroup<BF16>::GU; ++u) {
+            const int kk = k0 + KCH * u + VEC * q;
+            g.w[u] = *reinterpret_cast<const reg_t*>(wrow + (kk < K ? kk : 0));
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < WGroup<BF16>::GU; ++u) {
+            const int kk = k0 + KCH * u + VEC * q;
+            reg_t v;
+            if constexpr (BF16) v = ushort8{0, 0, 0, 0, 0, 0, 0, 0};
+            else v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 + KCH * u < K) {                       // wave-uniform: skip chunks wholly past K
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const w_t t = wrow[kk + e < K ? kk + e : 0];
+                    if constexpr (BF16) v[e] = t;
+                    else (&v.x)[e] = t;
+                }
+            }
+            g.w[u] = v;
+        }
+    }
+}
+
+// Zero the weights that lie outside [N x K] (see load_group).
+template <bool BF16>
+__device__ __forceinline__ void mask_group(WGroup<BF16>& g, int K, int N, int n, int k0, int q) {
+    constexpr int KCH = FM<BF16>::KCH;
+    constexpr int VEC = BF16 ? 8 : 4;
+#pragma unroll
+    for (int u = 0; u < WGroup<BF16>::GU; ++u) {
+        const int kk = k0 + KCH * u + VEC * q;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const bool ok = n < N && kk + e < K;
+            if constexpr (BF16) g.w[u][e] = ok ? g.w[u][e] : (unsigned short)0;
+            else (&g.w[u].x)[e] = ok ? (&g.w[u].x)[e] : 0.f;
+        }
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void mfma_chunk(floatx4& acc, const typename FM<BF16>::act_t* xrow, int k,
+                                           const typename WGroup<BF16>::reg_t& w) {
+    if constexpr (!BF16) {
+        // lane (row, q) feeds k = 4q..4q+3 of each 16-chunk to four MFMAs, one component each; x and
+        // W use the same assignment, so every k is multiplied exactly once
+        const float4 x = *reinterpret_cast<const float4*>(xrow + k);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, w.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, w.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, w.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, w.w, acc, 0, 0, 0);
+    } else {
+        const ushort8 xs = *reinterpret_cast<const ushort8*>(xrow + k);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xs), __builtin_bit_cast(bf16x8, w), acc,
+                                                       0, 0, 0);
+    }
+}
+
+// The layer table of the kernel arguments, copied once into scalar registers.  Lookups by a
+// (wave-uniform) run-time layer number are chains of scalar selects instead of dependent loads
+// from the argument buffer.
+struct LayerTab {
+    int w0, w1, w2, w3, w4;
+    const void *W0, *W1, *W2, *W3;
+    const float *b0, *b1, *b2, *b3;
+    int a0, a1, a2, a3;
+    int n_layers;
+
+    __device__ __forceinline__ explicit LayerTab(const rec_fused_mlp_args& a)
+        : w0(a.width[0]), w1(a.width[1]), w2(a.width[2]), w3(a.width[3]), w4(a.width[4]),
+          W0(a.W[0]), W1(a.W[1]), W2(a.W[2]), W3(a.W[3]),
+          b0(a.bias[0]), b1(a.bias[1]), b2(a.bias[2]), b3(a.bias[3]),
+          a0(a.act[0]), a1(a.act[1]), a2(a.act[2]), a3(a.act[3]), n_layers(a.n_layers) {
+        static_assert(REC_FUSED_MAX_LAYERS == 4, "LayerTab is written out for four layers");
+    }
+    __device__ __forceinline__ int w(int i) const { return i == 0 ? w0 : i == 1 ? w1 : i == 2 ? w2 : i == 3 ? w3 : w4; }
+    __device__ __forceinline__ const void* wt(int l) const { return l == 0 ? W0 : l == 1 ? W1 : l == 2 ? W2 : W3; }
+    __device__ __forceinline__ const float* b(int l) const { return l == 0 ? b0 : l == 1 ? b1 : l == 2 ? b2 : b3; }
+    __device__ __forceinline__ int ac(int l) const { return l == 0 ? a0 : l == 1 ? a1 : l == 2 ? a2 : a3; }
+};
+
+// What one wave does in one layer.  A layer has Np/16 column tiles.  With at least 16 tiles
+// wave w takes tiles w, w+16, ... over the whole of k.  With fewer, the spare waves split k:
+// ks waves share a tile, each taking a contiguous run of k-groups, and their partial tiles are
+// folded through LDS in wave order (fixed, so results are reproducible).  All fields are
+// wave-uniform.
+struct WavePlan {
+    int n_first, n_step, n_end;   // column tiles: n0 = n_first, n_first + n_step, ... < n_end
+    int k_begin, k_end;           // k-groups: k0 = k_begin, k_begin + GK, ... < k_end
+    int ks, kpart, pass_waves;    // split factor, this wave's part, waves per k-part
+};
+
+template <bool BF16>
+__device__ __forceinline__ WavePlan plan_layer(const LayerTab& t, int l, int wave) {
+    constexpr int KCH = FM<BF16>::KCH;
+    constexpr int GK = KCH * WGroup<BF16>::GU;
+    const int Kp = (t.w(l) + KCH - 1) / KCH * KCH;
+    const int Np = (t.w(l + 1) + KCH - 1) / KCH * KCH;
+    const int tiles = Np / 16, groups = (Kp + GK - 1) / GK;
+    int ks = 1;
+    while (ks * 2 * tiles <= FM_WAVES && ks * 2 <= groups) ks *= 2;
+    WavePlan p;
+    p.ks = ks;
+    p.pass_waves = FM_WAVES / ks;
+    p.kpart = wave / p.pass_waves;
+    const int gper = (groups + ks - 1) / ks;
+    p.k_begin = p.kpart * gper * GK;
+    p.k_end = (p.k_begin + gper * GK < Kp) ? p.k_begin + gper * GK : Kp;
+    p.n_first = (wave % p.pass_waves) * 16;
+    p.n_step = p.pass_waves * 16;
+    p.n_end = (p.k_begin < p.k_end) ? Np : 0;
+    return p;
+}
+
+// Position of a wave in its work list: layer, column tile, k-group.
+struct Cursor {
+    int l, n0, k0;
+    WavePlan p;
+};
+
+// First item of layer c.l or of the next layer in which the wave has work; false if none.
+template <bool BF16>
+__device__ __forceinline__ bool cursor_enter(Cursor& c, const LayerTab& t, int wave) {
+    while (c.l < t.n_layers) {
+        c.p = plan_layer<BF16>(t, c.l, wave);
+        if (c.p.n_first < c.p.n_end) {
+            c.n0 = c.p.n_first;
+            c.k0 = c.p.k_begin;
+            return true;
+        }
+        ++c.l;
+    }
+    return false;
+}
+
+template <bool BF16>
+__device__ __forceinline__ bool cursor_next(Cursor& c, const LayerTab& t, int wave) {
+    constexpr int GK = FM<BF16>::KCH * WGroup<BF16>::GU;
+    c.k0 += GK;
+    if (c.k0 < c.p.k_end) return true;
+    c.k0 = c.p.k_begin;
+    c.n0 += c.p.n_step;
+    if (c.n0 < c.p.n_end) return true;
+    ++c.l;
+    return cursor_enter<BF16>(c, t, wave);
+}
+
+// Bias, activation and store of one 16x16 tile.  MFMA 16x16 accumulator layout: register v of
+// lane l holds row 4*(l/16)+v, column l%16.  Hidden layers go to the LDS buffer of the next layer
+// (columns past N are written as zeros: they are that layer's k padding), the last one to memory.
+template <bool BF16>
+__device__ __forceinline__ void tile_out(const floatx4& acc, int n, int N, int q, const float* __restrict__ bias, int act,
+                                         bool last, typename FM<BF16>::act_t* out, const rec_fused_mlp_args& a, int m0) {
+    const float bv = (n < N) ? bias[n] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int r = 4 * q + v;
+        const float z = (n < N) ? rec_apply_act(acc[v] + bv, act) : 0.f;
+        if (!last) {
+            out[r * FM<BF16>::LDA + n] = to_act<BF16>(z);
+        } else if (n < N && m0 + r < a.B) {
+            if (a.y_bf16) static_cast<uint16_t*>(a.y)[(int64_t)(m0 + r) * a.ldy + n] = rec_f32_to_bf16_bits(z);
+            else static_cast<float*>(a.y)[(int64_t)(m0 + r) * a.ldy + n] = z;
+        }
+    }
+}
+
+// Weights do not depend on activations, so a wave always has the weights of its NEXT item in
+// flight -- across column tiles and across layer boundaries -- while it multiplies the current
+// one; the only exposed latencies are the first load and the input rows.  What bounds a block
+// is the bytes it keeps in flight, so all 16 waves are given weight rows to fetch.
+template <bool BF16>
+__global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_args a) {
+    typedef FM<BF16> C;
+    typedef typename C::act_t act_t;
+    constexpr int KCH = C::KCH;
+    constexpr int GU = WGroup<BF16>::GU;
+    constexpr int GK = KCH * GU;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * C::BUF_BYTES];
+    __shared__ float red[FM_WAVES * 4 * 64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m0 = blockIdx.x * FM_ROWS;
+    const int li = lane & 15, q = lane >> 4;
+    const LayerTab t(a);
+
+    Cursor nxt;
+    nxt.l = 0;
+    bool have_next = cursor_enter<BF16>(nxt, t, wave);
+    WGroup<BF16> gn;
+    if (have_next) load_group<BF16>(gn, t.wt(nxt.l), t.w(nxt.l), t.w(nxt.l + 1), nxt.n0, nxt.k0, li, q);
+
+    // stage the 16 input rows, zero-padded to a whole number of k-chunks.  The loads of a round
+    // are independent and issued together (wide ones when the rows allow), so the whole tile
+    // costs about one memory latency.
+    {
+        act_t* buf = reinterpret_cast<act_t*>(lds);
+        const int K0 = t.w0;
+        const int K0p = (K0 + KCH - 1) / KCH * KCH;
+        const bool rows16 = rec_dev_aligned(a.x, 16);
+        if (!a.x_bf16 && K0 % 4 == 0 && a.ldx % 4 == 0 && rows16) {
+            const float* __restrict__ x = static_cast<const float*>(a.x);
+            const int per_row = K0p / 4, total = FM_ROWS * per_row;
+            for (int e0 = 0; e0 < total; e0 += 4 * FM_THREADS) {
+                float4 v[4];
+                int r[4], c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = e0 + i * FM_THREADS + tid;
+                    r[i] = e / per_row;
+                    c[i] = (e - r[i] * per_row) * 4;
+                    const bool ok = e < total && m0 + r[i] < a.B && c[i] < K0;
+                    v[i] = *reinterpret_cast<const float4*>(x + (ok ? (int64_t)(m0 + r[i]) * a.ldx + c[i] : 0));
+                    if (!ok) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (e0 + i * FM_THREADS + tid < total) {
+                        act_t* d = buf + r[i] * C::LDA + c[i];
+                        d[0] = to_act<BF16>(v[i].x);
+                        d[1] = to_act<BF16>(v[i].y);
+                        d[2] = to_act<BF16>(v[i].z);
+                        d[3] = to_act<BF16>(v[i].w);
+                    }
+                }
+            }
+        } else if (BF16 && a.x_bf16 && K0 % 8 == 0 && a.ldx % 8 == 0 && rows16) {
+            const uint16_t* __restrict__ x = static_cast<const uint16_t*>(a.x);
+            const int per_row = K0p / 8, total = FM_ROWS * per_row;
+            for (int e0 = 0; e0 < total; e0 += 4 * FM_THREADS) {
+                ushort8 v[4];
+                int r[4], c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = e0 + i * FM_THREADS + tid;
+                    r[i] = e / per_row;
+                    c[i] = (e - r[i] * per_row) * 8;
+                    const bool ok = e < total && m0 + r[i] < a.B && c[i] < K0;
+                    v[i] = *reinterpret_cast<const ushort8*>(x + (ok ? (int64_t)(m0 + r[i]) * a.ldx + c[i] : 0));
+                    if (!ok) v[i] = ushort8{0, 0, 0, 0, 0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (e0 + i * FM_THREADS + tid < total)
+                        *reinterpret_cast<ushort8*>(reinterpret_cast<uint16_t*>(buf) + r[i] * C::LDA + c[i]) = v[i];
+            }
+        } else {
+            const int total = FM_ROWS * K0p;
+            for (int e0 = 0; e0 < total; e0 += 4 * FM_THREADS) {
+                float v[4];
+                int r[4], c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = e0 + i * FM_THREADS + tid;
+                    r[i] = e / K0p;
+                    c[i] = e - r[i] * K0p;
+                    const bool ok = e < total && m0 + r[i] < a.B && c[i] < K0;
+                    const int64_t off = ok ? (int64_t)(m0 + r[i]) * a.ldx + c[i] : 0;
+                    float xv;
+                    if (a.x_bf16) xv = __uint_as_float((uint32_t) static_cast<const uint16_t*>(a.x)[off] << 16);
+                    else xv = static_cast<const float*>(a.x)[off];
+                    v[i] = ok ? xv : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (e0 + i * FM_THREADS + tid < total) buf[r[i] * C::LDA + c[i]] = to_act<BF16>(v[i]);
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int l = 0; l < t.n_layers; ++l) {
+        const int K = t.w(l), N = t.w(l + 1);
+        const bool last = (l == t.n_layers - 1);
+        const int act = t.ac(l);
+        const act_t* in = reinterpret_cast<const act_t*>(lds + (l & 1) * C::BUF_BYTES);
+        act_t* out = reinterpret_cast<act_t*>(lds + ((l + 1) & 1) * C::BUF_BYTES);
+        const float* __restrict__ bias = t.b(l);
+        const act_t* xrow = in + li * C::LDA + (BF16 ? 8 : 4) * q;
+        const WavePlan p = plan_layer<BF16>(t, l, wave);
+
+        // With ks > 1 a wave owns at most one (tile, k-part), so the tile loop runs at most once
+        // and `acc` still holds that partial tile after it.
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int n0 = p.n_first; n0 < p.n_end; n0 += p.n_step) {
+            const int n = n0 + li;
+            acc = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int k0 = p.k_begin; k0 < p.k_end; k0 += GK) {
+                WGroup<BF16> g = gn;                             // item (l, n0, k0)
+                have_next = cursor_next<BF16>(nxt, t, wave);
+                if (have_next) load_group<BF16>(gn, t.wt(nxt.l), t.w(nxt.l), t.w(nxt.l + 1), nxt.n0, nxt.k0, li, q);
+                // only a tile on the edge of W holds lanes to discard
+                if (n0 + 16 > N || k0 + GK > K) mask_group<BF16>(g, K, N, n, k0, q);
+                if (k0 + GK <= p.k_end) {
+#pragma unroll
+                    for (int u = 0; u < GU; ++u) mfma_chunk<BF16>(acc, xrow, k0 + KCH * u, g.w[u]);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < GU; ++u)
+                        if (k0 + KCH * u < p.k_end) mfma_chunk<BF16>(acc, xrow, k0 + KCH * u, g.w[u]);
+                }
+            }
+            if (p.ks == 1) tile_out<BF16>(acc, n0 + li, N, q, bias, act, last, out, a, m0);
+        }
+        if (p.ks > 1) {
+            const bool active = p.n_first < p.n_end;
+            if (active && p.kpart > 0) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(wave * 4 + v) * 64 + lane] = acc[v];
+            }
+            __syncthreads();
+            if (active && p.kpart == 0) {
+                for (int s2 = 1; s2 < p.ks; ++s2) {
+                    const int w2 = wave + s2 * p.pass_waves;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[v] += red[(w2 * 4 + v) * 64 + lane];
+                }
+                tile_out<BF16>(acc, p.n_first + li, N, q, bias, act, last, out, a, m0);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, hipStream_t s) {
+    const unsigned blocks = (unsigned)((a.B + FM_ROWS - 1) / FM_ROWS);
+    if (dt == REC_BF16)
+        hipLaunchKernelGGL(fused_mlp_kernel<true>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
+    else
+        hipLaunchKernelGGL(fused_mlp_kernel<false>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
+    REC_CHECK_LAUNCH();
+    return REC_OK;
+}

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "rec.h"
 
 #define REC_WAVE 64
@@ -29,3 +31,29 @@ __device__ __forceinline__ float rec_apply_act(float z, int act) {
     if (act == REC_ACT_SIGMOID) return 1.0f / (1.0f + expf(-z));
     return z;
 }
+
+__device__ __forceinline__ bool rec_dev_aligned(const void* p, size_t a) {
+    return (reinterpret_cast<uintptr_t>(p) % a) == 0;
+}
+
+// ---- several narrow FC layers in one launch (fc_fused.hip) ----------------------------------
+#define REC_FUSED_MAX_LAYERS 4
+#define REC_FUSED_MAX_WIDTH_F32 512      // widest activation row kept in LDS, fp32 stacks
+#define REC_FUSED_MAX_WIDTH_BF16 1024    // ... and bf16 stacks
+
+struct rec_fused_mlp_args {
+    const void* W[REC_FUSED_MAX_LAYERS];      // [width[l+1]][width[l]] row-major, fp32 or bf16 patterns
+    const float* bias[REC_FUSED_MAX_LAYERS];
+    int32_t width[REC_FUSED_MAX_LAYERS + 1];
+    int32_t act[REC_FUSED_MAX_LAYERS];
+    int32_t n_layers;
+    const void* x;                            // fp32, or bf16 patterns when x_bf16 (bf16 stacks only)
+    int32_t x_bf16;
+    int64_t ldx;
+    void* y;                                  // fp32, or bf16 patterns when y_bf16
+    int32_t y_bf16;
+    int64_t ldy;
+    int32_t B;
+};
+
+rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, hipStream_t s);
