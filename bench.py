@@ -19,6 +19,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
+# HBM bytes per launch of the pooling kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled
+# by a copy-shaped reference dispatch (see profiles/sls_kernel_rmc2_counters.md).  Valid for the
+# sls_kernel these were taken with; set an entry to None when that kernel changes.
+SLS_COUNTED_TRAFFIC_BYTES = {"rmc2": 316.4e6, "rmc2-uniform": 705.9e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -28,6 +33,11 @@ def parse():
     ap.add_argument("--workload", default="rmc2", choices=["tiny", "rmc1", "rmc2", "rmc2-uniform", "rmc3"])
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-batch-size", action="store_true",
+                    help="skip the short runs at sub-batch sizes 16/64/256 (keeps every launch of a profile at full batch)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain device copies of 256 MiB (reference dispatches for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--sweep", action="store_true",
                     help="also replay 2000 lognormal-sized queries split into sub-batches of 16/64/256/1024")
     return ap.parse_args()
@@ -139,13 +149,13 @@ def main():
     sls_bytes = float(np.mean([sls_algorithmic_bytes(cfg, n, cfg.B) for n in used]))
     sls_gbs = sls_bytes / sls_sec / 1e9
     roofline = {"bound": "hbm", "kernel": "sls_kernel", "achieved": sls_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": sls_gbs / HBM_PEAK_GBS, "traffic": None, "us_per_launch": sls_sec * 1e6,
+                "frac": sls_gbs / HBM_PEAK_GBS, "traffic": SLS_COUNTED_TRAFFIC_BYTES.get(cfg.name), "us_per_launch": sls_sec * 1e6,
                 "algorithmic_bytes_per_launch": sls_bytes}
 
     # samples/s per sub-batch size (the batch sizes of the query-size sweep)
     per_b = {}
     for Bs in synth.SWEEP_BATCH_SIZES:
-        if Bs > cfg.B:
+        if Bs > cfg.B or a.no_per_batch_size:
             continue
         subs = [workload.DeviceBatch(workload.slice_batch(host_batches[k % len(host_batches)], cfg.T, 0, Bs))
                 for k in range(4)]
@@ -165,6 +175,28 @@ def main():
                       "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
                       "bottom": list(cfg.bottom), "top": list(cfg.top), "distinct_batches": len(dbs)},
            "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "setup_s": setup_s}
+
+    if a.copy_calibration:
+        # Reference dispatches of known size for scaling FETCH_SIZE / WRITE_SIZE:
+        # (1) the pooling kernel itself as a plain copy -- one table, bag i = [row i], so it reads
+        #     n rows (+ n indices, n+1 offsets) and writes n rows with the request pattern of the real run;
+        # (2) the runtime's device-to-device copy of 256 MiB.
+        n = min(cfg.R, 500_000)
+        one = rec.Tables([model.tables.tensors[0]])
+        idx = torch.arange(n, dtype=torch.int32, device="cuda")
+        off = torch.arange(n + 1, dtype=torch.int64, device="cuda")
+        dst_rows = torch.empty((n, 1, cfg.D), dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            rec.sls_forward_offsets(one, idx, off, n, out=dst_rows, out_stride_b=cfg.D, out_stride_t=cfg.D)
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"sls_as_copy": {"grid_threads": ((n + 3) // 4) * 256,
+                                                   "read_bytes": n * (4 * cfg.D + 4) + 8 * (n + 1),
+                                                   "write_bytes": n * 4 * cfg.D},
+                                   "memcpy_d2d_bytes": int(src.numel())}
 
     if a.sweep:
         out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
