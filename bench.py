@@ -152,6 +152,28 @@ def main():
                 "frac": sls_gbs / HBM_PEAK_GBS, "traffic": SLS_COUNTED_TRAFFIC_BYTES.get(cfg.name), "us_per_launch": sls_sec * 1e6,
                 "algorithmic_bytes_per_launch": sls_bytes}
 
+    sls_roofline = roofline
+    if cfg.bf16:
+        # MLP-dominated workload: the dominant kernel is the first (widest) Dense-FC layer, a bf16
+        # MFMA contraction [B x F] . [n1 x F]^T.  Timed alone between events: the layer call launches
+        # the tiled GEMM and, when k is split across blocks, the small kernel that folds the partials.
+        W0, b0 = model.bottom_W[0], model.bottom_b[0]
+        n1, F = W0.shape
+        y1 = torch.empty((cfg.B, n1), dtype=torch.float32, device="cuda")
+        ws1 = torch.empty(max(256, rec.mlp_workspace_bytes([F, n1], cfg.B, rec.BF16)), dtype=torch.uint8, device="cuda")
+
+        def layer1(i):
+            rec.mlp_forward([W0], [b0], dbs[i % len(dbs)].dense, rec.ACT_RELU, rec.ACT_RELU, wdtype=rec.BF16, y=y1,
+                            ldy=n1, workspace=ws1)
+
+        l1_sec = event_time(layer1, a.steps, a.warmup, torch)
+        flops = 2.0 * cfg.B * F * n1
+        tf = flops / l1_sec / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (+ splitk_reduce_kernel)", "achieved": tf,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "us_per_launch": l1_sec * 1e6, "flops_per_launch": flops,
+                    "layer": f"{cfg.B}x{F} . ({n1}x{F})^T bf16 operands, fp32 accumulate"}
+
     # samples/s per sub-batch size (the batch sizes of the query-size sweep)
     per_b = {}
     for Bs in synth.SWEEP_BATCH_SIZES:
@@ -175,6 +197,8 @@ def main():
                       "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
                       "bottom": list(cfg.bottom), "top": list(cfg.top), "distinct_batches": len(dbs)},
            "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "setup_s": setup_s}
+    if roofline is not sls_roofline:
+        out["sls_roofline"] = sls_roofline
 
     if a.copy_calibration:
         # Reference dispatches of known size for scaling FETCH_SIZE / WRITE_SIZE:

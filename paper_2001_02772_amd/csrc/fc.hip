@@ -309,9 +309,23 @@ void choose_shape(int M, int N, int K, bool bf16, int* shape, int* ksplit) {
     *ksplit = ks;
 }
 
+// Bytes of fp32 partial tiles the stack needs for layers that take the large-tile bf16 kernel.
+size_t splitk_bytes(const int32_t* widths, int32_t n_layers, int32_t B, rec_dtype dt) {
+    size_t mx = 0;
+    if (dt != REC_BF16) return 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const size_t b = rec_gemm_bf16_partial_bytes(B, widths[l + 1], widths[l]);
+        mx = b > mx ? b : mx;
+    }
+    return mx;
+}
+
 rec_status launch_layer(const void* x, bool x_bf16, int64_t ldx, const void* W, rec_dtype dt, const float* bias,
                         int32_t B, int32_t n_in, int32_t n_out, int act, void* y, bool y_bf16, int64_t ldy,
-                        hipStream_t s) {
+                        float* partial, hipStream_t s) {
+    if (dt == REC_BF16 && rec_gemm_bf16_split(B, n_out, n_in) >= 1 && rec_aligned(x, 16) && rec_aligned(W, 16) &&
+        ldx % (x_bf16 ? 8 : 4) == 0)
+        return rec_gemm_bf16_launch(x, x_bf16, ldx, W, bias, y, y_bf16, ldy, partial, B, n_out, n_in, act, s);
     int shape, ksplit;
     choose_shape(B, n_out, n_in, dt == REC_BF16, &shape, &ksplit);
     if (dt == REC_F32) {
@@ -333,7 +347,9 @@ extern "C" {
 
 size_t rec_mlp_workspace_bytes(const int32_t* widths, int32_t n_layers, int32_t B, rec_dtype wdtype) {
     if (!widths || n_layers < 1 || B < 0) return 0;
-    return 2 * hidden_buffer_bytes(widths, n_layers, B, wdtype);
+    for (int32_t l = 0; l <= n_layers; ++l)
+        if (widths[l] < 1) return 0;
+    return 2 * hidden_buffer_bytes(widths, n_layers, B, wdtype) + splitk_bytes(widths, n_layers, B, wdtype);
 }
 
 rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const int32_t* widths,
@@ -353,8 +369,9 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
     if (!x || !y) return REC_ERR_NULL;
     if (ldx < widths[0] || ldy < widths[n_layers]) return REC_ERR_BAD_SHAPE;
     const size_t half = hidden_buffer_bytes(widths, n_layers, B, wdtype);
-    if (n_layers > 1 && (!workspace || !rec_aligned(workspace, 256) || workspace_bytes < 2 * half))
-        return REC_ERR_WORKSPACE;
+    const size_t need = 2 * half + splitk_bytes(widths, n_layers, B, wdtype);
+    if (need > 0 && (!workspace || !rec_aligned(workspace, 256) || workspace_bytes < need)) return REC_ERR_WORKSPACE;
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * half);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf = (wdtype == REC_BF16);
     const void* cur = x;
@@ -393,7 +410,7 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
             st = rec_fused_mlp_launch(a, wdtype, s);
         } else {
             st = launch_layer(cur, cur_bf16, ld, W[l], wdtype, bias[l], B, widths[l], widths[l + 1],
-                              last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, s);
+                              last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, partial, s);
         }
         if (st != REC_OK) return st;
         cur = dst;

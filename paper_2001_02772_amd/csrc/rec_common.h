@@ -57,3 +57,10 @@ struct rec_fused_mlp_args {
 };
 
 rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, hipStream_t s);
+
+// ---- large bf16 layers (gemm_bf16.hip) --------------------------------------------------------
+int rec_gemm_bf16_split(int M, int N, int K);                    // 0: kernel does not apply
+size_t rec_gemm_bf16_partial_bytes(int M, int N, int K);         // fp32 partial tiles for the k split
+rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const void* W, const float* bias, void* y,
+                                bool y_bf16, int64_t ldy, float* partial, int M, int N, int K, int act,
+                                hipStream_t s);

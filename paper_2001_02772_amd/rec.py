@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "librec.so")
-SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("sls.hip", "fc.hip", "fc_fused.hip", "interact.hip", "model.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("sls.hip", "fc.hip", "fc_fused.hip", "gemm_bf16.hip", "interact.hip", "model.hip")]
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_NEGATIVE_LENGTH, ERR_LENGTHS_MISMATCH, ERR_INDEX_RANGE, \
     ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(9)

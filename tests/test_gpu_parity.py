@@ -188,8 +188,10 @@ def test_mlp_f32_exact_cases(rec):
 
 @pytest.mark.parametrize("widths,B", [((2560, 1024, 256, 32), 128), ((87, 512, 256, 1), 300), ((64, 8), 5),
                                       ((100, 70, 3), 65), ((20, 24, 28, 32, 36, 40, 3), 50),
-                                      ((64, 32, 1100, 16), 40), ((1024, 128, 9), 17)])
+                                      ((64, 32, 1100, 16), 40), ((1024, 128, 9), 17),
+                                      ((512, 700), 300), ((512, 1024, 640, 8), 400), ((2560, 1024), 1024)])
 def test_mlp_bf16_vs_oracle(rec, widths, B):
+    oracle.set_threads(16)
     p = synth.mlp_params(widths, stack=4)
     x = rng.normal(size=(B, widths[0])).astype(np.float32)
     W, b = [rec.f32_to_bf16(dev(w)) for w in p.W], [dev(v) for v in p.b]
