@@ -148,7 +148,8 @@ def test_sls_is_deterministic(rec):
 
 # ------------------------------------------------------------------ interaction
 
-@pytest.mark.parametrize("V,D,B", [(2, 4, 3), (9, 32, 64), (11, 32, 100), (41, 64, 33), (27, 128, 5)])
+@pytest.mark.parametrize("V,D,B", [(2, 4, 3), (9, 32, 64), (11, 32, 100), (41, 64, 33), (27, 128, 5), (33, 12, 7),
+                                   (65, 64, 9), (128, 100, 3), (100, 256, 2), (32, 8, 1025)])
 def test_interact_vs_oracle(rec, V, D, B):
     v = rng.normal(size=(B, V, D)).astype(np.float32)
     got = rec.interact(dev(v)).cpu().numpy()
