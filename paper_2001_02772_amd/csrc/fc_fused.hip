@@ -40,7 +40,7 @@ __device__ __forceinline__ typename FM<BF16>::act_t to_act(float v) {
 // One pipeline item: the weights a lane needs for GU consecutive k-chunks of one 16-column tile.
 template <bool BF16>
 struct WGroup {
-    static constexpr int GU = 8;
+    static constexpr int GU = 4;
     typedef typename std::conditional<BF16, ushort8, float4>::type reg_t;
     reg_t w[GU];
 };
@@ -152,6 +152,7 @@ struct WavePlan {
     int n_first, n_step, n_end;   // column tiles: n0 = n_first, n_first + n_step, ... < n_end
     int k_begin, k_end;           // k-groups: k0 = k_begin, k_begin + GK, ... < k_end
     int ks, kpart, pass_waves;    // split factor, this wave's part, waves per k-part
+    int parts;                    // k-parts that actually hold k-groups (<= ks)
 };
 
 template <bool BF16>
@@ -168,6 +169,7 @@ __device__ __forceinline__ WavePlan plan_layer(const LayerTab& t, int l, int wav
     p.pass_waves = FM_WAVES / ks;
     p.kpart = wave / p.pass_waves;
     const int gper = (groups + ks - 1) / ks;
+    p.parts = (groups + gper - 1) / gper;
     p.k_begin = p.kpart * gper * GK;
     p.k_end = (p.k_begin + gper * GK < Kp) ? p.k_begin + gper * GK : Kp;
     p.n_first = (wave % p.pass_waves) * 16;
@@ -374,7 +376,7 @@ __global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_arg
             }
             __syncthreads();
             if (active && p.kpart == 0) {
-                for (int s2 = 1; s2 < p.ks; ++s2) {
+                for (int s2 = 1; s2 < p.parts; ++s2) {
                     const int w2 = wave + s2 * p.pass_waves;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) acc[v] += red[(w2 * 4 + v) * 64 + lane];

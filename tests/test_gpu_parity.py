@@ -165,7 +165,8 @@ def test_interact_vs_oracle(rec, V, D, B):
 @pytest.mark.parametrize("widths,B", [((13, 64, 32), 64), ((13, 256, 128, 64), 100), ((87, 256, 64, 1), 257),
                                       ((884, 512, 128, 1), 1024), ((5, 1), 1), ((70, 33, 65, 2), 63),
                                       ((20, 24, 28, 32, 36, 40, 3), 50), ((64, 32, 1000, 16), 40),
-                                      ((512, 512, 7), 17), ((600, 64, 700, 5), 33)])
+                                      ((512, 512, 7), 17), ((600, 64, 700, 5), 33),
+                                      ((320, 8), 33), ((448, 40, 17), 20), ((192, 100), 16), ((384, 24), 5)])
 def test_mlp_f32_vs_oracle(rec, widths, B):
     p = synth.mlp_params(widths, stack=3)
     x = rng.uniform(0, 1, size=(B, widths[0])).astype(np.float32)
@@ -190,7 +191,8 @@ def test_mlp_f32_exact_cases(rec):
 @pytest.mark.parametrize("widths,B", [((2560, 1024, 256, 32), 128), ((87, 512, 256, 1), 300), ((64, 8), 5),
                                       ((100, 70, 3), 65), ((20, 24, 28, 32, 36, 40, 3), 50),
                                       ((64, 32, 1100, 16), 40), ((1024, 128, 9), 17),
-                                      ((512, 700), 300), ((512, 1024, 640, 8), 400), ((2560, 1024), 1024)])
+                                      ((512, 700), 300), ((512, 1024, 640, 8), 400), ((2560, 1024), 1024),
+                                      ((640, 8), 33), ((1024, 40, 17), 20), ((896, 100), 16)])
 def test_mlp_bf16_vs_oracle(rec, widths, B):
     oracle.set_threads(16)
     p = synth.mlp_params(widths, stack=4)
