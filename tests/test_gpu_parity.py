@@ -191,7 +191,7 @@ def test_mlp_f32_exact_cases(rec):
 @pytest.mark.parametrize("widths,B", [((2560, 1024, 256, 32), 128), ((87, 512, 256, 1), 300), ((64, 8), 5),
                                       ((100, 70, 3), 65), ((20, 24, 28, 32, 36, 40, 3), 50),
                                       ((64, 32, 1100, 16), 40), ((1024, 128, 9), 17),
-                                      ((512, 700), 300), ((512, 1024, 640, 8), 400), ((2560, 1024), 1024),
+                                      ((512, 700), 600), ((512, 1024, 640, 8), 900), ((2560, 1024), 1024),
                                       ((640, 8), 33), ((1024, 40, 17), 20), ((896, 100), 16)])
 def test_mlp_bf16_vs_oracle(rec, widths, B):
     oracle.set_threads(16)
