@@ -87,13 +87,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void offsets_kernel(const int32_t* __
             if (vec_ok) {
                 const int4* __restrict__ len4 = reinterpret_cast<const int4*>(len);
                 const int64_t nv = before / 4;
-                for (int64_t i = tid; i < nv; i += 8 * SCAN_THREADS) {
-                    int4 q[8];
+                for (int64_t i = tid; i < nv; i += 16 * SCAN_THREADS) {
+                    int4 q[16];
 #pragma unroll
-                    for (int k = 0; k < 8; ++k)
-                        q[k] = (i + k * SCAN_THREADS < nv) ? len4[i + k * SCAN_THREADS] : make_int4(0, 0, 0, 0);
+                    for (int k = 0; k < 16; ++k) {        // unconditional loads from clamped addresses
+                        const int64_t j = i + k * SCAN_THREADS;
+                        q[k] = len4[j < nv ? j : nv - 1];
+                    }
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) part += (int64_t)q[k].x + q[k].y + q[k].z + q[k].w;
+                    for (int k = 0; k < 16; ++k)
+                        if (i + k * SCAN_THREADS < nv) part += (int64_t)q[k].x + q[k].y + q[k].z + q[k].w;
                 }
             } else {
                 for (int64_t i = tid; i < before; i += 8 * SCAN_THREADS) {
