@@ -39,6 +39,15 @@ def lib():
         _lib.orc_bf16_round.argtypes = [C.c_float]
         _lib.orc_split_query.restype = C.c_int64
         _lib.orc_split_query.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+        _lib.orc_query_service.restype = C.c_double
+        _lib.orc_query_service.argtypes = [C.c_int64, C.c_int64, C.c_void_p]
+        _lib.orc_fifo_latencies.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.orc_percentile.restype = C.c_double
+        _lib.orc_percentile.argtypes = [C.c_void_p, C.c_int64, C.c_double]
+        _lib.orc_max_qps.restype = C.c_double
+        _lib.orc_max_qps.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_double, C.c_int32]
+        _lib.orc_hill_climb.restype = C.c_int64
+        _lib.orc_hill_climb.argtypes = [C.c_void_p, C.c_int64]
     return _lib
 
 
@@ -164,3 +173,36 @@ def split_query(n: int, Bsz: int):
     start, count = np.empty(k, dtype=np.int64), np.empty(k, dtype=np.int64)
     lib().orc_split_query(n, Bsz, _p(start), _p(count))
     return list(zip(start.tolist(), count.tolist()))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def query_service(n: int, B: int, table) -> float:
+    """table[b] = seconds for one request of b items (index 0 unused)."""
+    table = _f64(table)
+    assert table.size > B
+    return lib().orc_query_service(n, B, _p(table))
+
+
+def fifo_latencies(arrival, service):
+    arrival, service = _f64(arrival), _f64(service)
+    lat = np.empty_like(arrival)
+    lib().orc_fifo_latencies(_p(arrival), _p(service), arrival.size, _p(lat))
+    return lat
+
+
+def percentile(x, p: float) -> float:
+    x = _f64(x)
+    return lib().orc_percentile(_p(x), x.size, p)
+
+
+def max_qps(unit_arrival, service, p: float, sla: float, iters: int = 40) -> float:
+    unit_arrival, service = _f64(unit_arrival), _f64(service)
+    return lib().orc_max_qps(_p(unit_arrival), _p(service), service.size, p, sla, iters)
+
+
+def hill_climb(qps) -> int:
+    qps = _f64(qps)
+    return lib().orc_hill_climb(_p(qps), qps.size)

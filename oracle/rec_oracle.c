@@ -253,3 +253,91 @@ int64_t orc_split_query(int64_t n, int64_t Bsz, int64_t* start, int64_t* count) 
     }
     return k;
 }
+
+/* ------------------------------------------------------------------------
+ * Query serving and the batch-size hill climb (Sections III-C, IV-A, IV-C).
+ * ---------------------------------------------------------------------- */
+
+/* Time to serve a query of n items cut into requests of size B (Section IV-A): floor(n/B)
+ * requests of B items and one of n mod B items, run one after another on one device.
+ * t[b] = seconds for one request of b items, b = 1..B (t[0] unused). */
+double orc_query_service(int64_t n, int64_t B, const double* t) {
+    double s = 0.0;
+    for (int64_t k = 0; k < n / B; ++k) s += t[B];
+    if (n % B) s += t[n % B];
+    return s;
+}
+
+/* Queries served first-come-first-served by one device: a query starts when it has arrived
+ * and the previous one has finished; its latency is finish - arrival (queueing included). */
+void orc_fifo_latencies(const double* arrival, const double* service, int64_t n, double* latency) {
+    double prev_finish = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const double start = (i > 0 && prev_finish > arrival[i]) ? prev_finish : arrival[i];
+        prev_finish = start + service[i];
+        latency[i] = prev_finish - arrival[i];
+    }
+}
+
+static int cmp_double(const void* a, const void* b) {
+    const double x = *(const double*)a, y = *(const double*)b;
+    return (x > y) - (x < y);
+}
+
+/* Nearest-rank percentile: the smallest sample v such that at least a fraction p of the
+ * samples is <= v, i.e. sorted[ceil(p*n) - 1].  p in (0, 1]. */
+double orc_percentile(const double* x, int64_t n, double p) {
+    double* s = (double*)malloc(sizeof(double) * (size_t)n);
+    memcpy(s, x, sizeof(double) * (size_t)n);
+    qsort(s, (size_t)n, sizeof(double), cmp_double);
+    int64_t k = (int64_t)ceil(p * (double)n) - 1;
+    if (k < 0) k = 0;
+    if (k > n - 1) k = n - 1;
+    const double v = s[k];
+    free(s);
+    return v;
+}
+
+static int orc_rate_ok(const double* unit_arrival, const double* service, int64_t n, double p, double sla,
+                       double rate, double* arr, double* lat) {
+    for (int64_t i = 0; i < n; ++i) arr[i] = unit_arrival[i] / rate;
+    orc_fifo_latencies(arr, service, n, lat);
+    return orc_percentile(lat, n, p) <= sla;
+}
+
+/* Latency-bounded throughput (Section III-B: QPS under a p95 tail-latency target): the largest
+ * arrival rate (queries/s) at which the p-th percentile latency stays <= sla.  Arrivals are
+ * unit_arrival[i] / rate (unit_arrival = arrival times of a rate-1 Poisson process), so a higher
+ * rate only compresses the same arrival pattern and latencies grow monotonically with it.
+ * 0 if the target is missed even without queueing.  The rate is bracketed by doubling from 1
+ * (halving if 1 is already too fast), then bisected `iters` times; the feasible end is returned. */
+double orc_max_qps(const double* unit_arrival, const double* service, int64_t n, double p, double sla, int32_t iters) {
+    if (n <= 0) return 0.0;
+    if (orc_percentile(service, n, p) > sla) return 0.0;
+    double* arr = (double*)malloc(sizeof(double) * (size_t)n);
+    double* lat = (double*)malloc(sizeof(double) * (size_t)n);
+    double lo = 1.0, hi = 1.0;
+    if (orc_rate_ok(unit_arrival, service, n, p, sla, 1.0, arr, lat)) {
+        hi = 2.0;
+        while (hi < 1e15 && orc_rate_ok(unit_arrival, service, n, p, sla, hi, arr, lat)) { lo = hi; hi *= 2.0; }
+    } else {
+        lo = 0.5;
+        while (lo > 1e-15 && !orc_rate_ok(unit_arrival, service, n, p, sla, lo, arr, lat)) { hi = lo; lo *= 0.5; }
+    }
+    for (int32_t k = 0; k < iters; ++k) {
+        const double mid = 0.5 * (lo + hi);
+        if (orc_rate_ok(unit_arrival, service, n, p, sla, mid, arr, lat)) lo = mid; else hi = mid;
+    }
+    free(arr);
+    free(lat);
+    return lo;
+}
+
+/* Batch-size hill climb (Section IV-C): start at the first candidate (unit batch size) and move
+ * to the next larger one while the achievable QPS improves; stop at the first step that does not
+ * improve it.  qps[i] = achievable QPS with the i-th candidate batch size.  Returns the index kept. */
+int64_t orc_hill_climb(const double* qps, int64_t n_candidates) {
+    int64_t i = 0;
+    while (i + 1 < n_candidates && qps[i + 1] > qps[i]) ++i;
+    return i;
+}

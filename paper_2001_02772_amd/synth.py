@@ -36,7 +36,7 @@ _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
 
 # stream kinds (stream id = kind * 2**20 + index)
-K_DENSE, K_LENGTHS, K_INDICES, K_TABLE, K_PERM, K_WEIGHT, K_BIAS, K_QUERY = range(8)
+K_DENSE, K_LENGTHS, K_INDICES, K_TABLE, K_PERM, K_WEIGHT, K_BIAS, K_QUERY, K_ARRIVAL = range(9)
 
 
 def stream_id(kind: int, index: int = 0) -> int:
@@ -127,6 +127,13 @@ def lognormal_query_sizes(seed, count, mu=4.5, sigma=1.0, lo=1, hi=1000) -> np.n
     u2 = _u53(draws_at(seed, st, c * np.uint64(2) + np.uint64(1)))
     z = np.sqrt(-2.0 * np.log(1.0 - u1)) * np.cos(2.0 * math.pi * u2)
     return np.clip(np.rint(np.exp(mu + sigma * z)), lo, hi).astype(np.int64)
+
+
+def unit_poisson_arrivals(seed, count) -> np.ndarray:
+    """Arrival times (float64, increasing) of a rate-1 Poisson process: cumulative sums of
+    unit-mean exponential gaps -ln(1-u).  Divide by a rate to get arrivals at that rate."""
+    u = _u53(draws(seed, stream_id(K_ARRIVAL), 0, count))
+    return np.cumsum(-np.log(1.0 - u))
 
 
 # --------------------------------------------------------------------------

@@ -30,6 +30,14 @@ MUTATIONS = {
     "model_top_uses_relu_last": ("ORC_ACT_RELU, ORC_ACT_SIGMOID, inter", "ORC_ACT_RELU, ORC_ACT_RELU, inter"),
     "model_sls_into_slot0": ("vecs + D, (int64_t)V * D, D, NULL, NULL", "vecs, (int64_t)V * D, D, NULL, NULL"),
     "split_drops_tail": ("(n - s < Bsz) ? n - s : Bsz", "Bsz"),
+    "service_drops_remainder": ("if (n % B) s += t[n % B];", ""),
+    "fifo_ignores_queue": ("(i > 0 && prev_finish > arrival[i]) ? prev_finish : arrival[i]", "arrival[i]"),
+    "fifo_latency_excludes_wait": ("latency[i] = prev_finish - arrival[i];", "latency[i] = service[i];"),
+    "percentile_off_by_one": ("(int64_t)ceil(p * (double)n) - 1;", "(int64_t)ceil(p * (double)n);"),
+    "max_qps_returns_infeasible_end": ("    free(lat);\n    return lo;", "    free(lat);\n    return hi;"),
+    "hill_climb_accepts_ties": ("qps[i + 1] > qps[i]", "qps[i + 1] >= qps[i]"),
+    "hill_climb_global_max": ("while (i + 1 < n_candidates && qps[i + 1] > qps[i]) ++i;",
+                              "for (int64_t j = 1; j < n_candidates; ++j) if (qps[j] > qps[i]) i = j;"),
 }
 
 
@@ -44,7 +52,8 @@ def test_pins_catch_planted_mistake(name, tmp_path):
     subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-o", str(lib), str(mutated), "-lm"])
     env = dict(os.environ, REC_ORACLE_LIB=str(lib))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        os.path.join(ROOT, "tests", "test_oracle_sched_pins.py")],
                        env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert r.returncode != 0, f"pins did not notice mutation {name}"
     assert "failed" in r.stdout
