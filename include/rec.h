@@ -183,6 +183,63 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
                              int64_t n_indices, const int32_t* lengths, int32_t B, float* prob,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- query serving and batch-size tuning -------------------------------------
+ * Section III-C: queries arrive as a Poisson process and carry a number of candidate items
+ * (the query size); Section IV-A: a query is split into requests of the chosen batch size;
+ * Section III-B: the figure of merit is the query rate sustained while the p95 query latency
+ * stays under a target; Section IV-C: the batch size is tuned by hill climbing on that rate.
+ * All arrays in this group are HOST arrays of doubles (seconds, queries/s). */
+
+/* Time to serve a query of n items as floor(n/batch) requests of `batch` items plus one of
+ * n mod batch items, one after another: table[b] = seconds for one request of b items,
+ * b = 1..batch (table[0] unused).  NaN if n < 0, batch < 1 or table is NULL. */
+double rec_sched_query_service(int64_t n, int64_t batch, const double* table);
+
+/* One device serving queries first-come-first-served: query i starts at max(arrival[i],
+ * finish of query i-1) and takes service[i]; latency[i] = finish - arrival[i].  Arrivals must be
+ * non-decreasing. */
+rec_status rec_sched_fifo_latencies(const double* arrival, const double* service, int64_t n, double* latency);
+
+/* Nearest-rank percentile: the smallest sample v with at least a fraction p of the samples
+ * <= v, i.e. sorted[ceil(p*n) - 1]; p in (0, 1].  NaN if n < 1 or p out of range. */
+double rec_sched_percentile(const double* x, int64_t n, double p);
+
+/* Latency-bounded throughput: the largest rate r (queries/s) for which the p-th percentile of
+ * the FIFO latencies with arrivals unit_arrival[i] / r stays <= sla, where unit_arrival are the
+ * arrival times of a rate-1 Poisson process.  0 if the percentile of `service` alone exceeds sla.
+ * Search: r = 1 is tested; feasible -> double until infeasible (cap 1e15), infeasible -> halve
+ * until feasible (floor 1e-15); then `iters` bisection steps; the feasible end is returned.
+ * NaN on bad arguments. */
+double rec_sched_max_qps(const double* unit_arrival, const double* service, int64_t n, double p, double sla,
+                         int32_t iters);
+
+/* Hill climb over candidate batch sizes in increasing order (first = unit batch size):
+ * qps[i] = achievable rate with candidate i.  Moves to the next candidate until the rate
+ * degrades: stops at the first step that lowers it (steps that leave it unchanged are taken, so
+ * the climb crosses batch sizes that all miss the latency target).  Returns the index kept,
+ * -1 if n_candidates < 1 or qps is NULL. */
+int64_t rec_sched_hill_climb(const double* qps, int64_t n_candidates);
+
+/* One request = one rec_model_forward call: inputs as for rec_model_forward (all DEV). */
+typedef struct {
+    const float* dense;
+    const int32_t* indices;
+    int64_t n_indices;
+    const int32_t* lengths;
+    int32_t B;
+} rec_request;
+
+/* Open-loop replay of a query trace on one device (SYNCHRONOUS, busy-waits on the host clock):
+ * query q, made of requests[query_first[q] .. query_first[q+1]), is submitted to `stream` when
+ * the host clock reaches arrival_s[q] (seconds from the start of the call, non-decreasing) and
+ * never before; requests run in order.  latency_s[q] = completion of the query's last request
+ * (device timestamp) - arrival_s[q].  prob: DEV fp32 [max request B], overwritten by every
+ * request; workspace >= rec_model_workspace_bytes(m, max request B).  HOST: requests,
+ * query_first [n_queries + 1], arrival_s, latency_s [n_queries]. */
+rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, const int64_t* query_first,
+                           const double* arrival_s, int64_t n_queries, float* prob, void* workspace,
+                           size_t workspace_bytes, void* stream, double* latency_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -334,10 +334,12 @@ double orc_max_qps(const double* unit_arrival, const double* service, int64_t n,
 }
 
 /* Batch-size hill climb (Section IV-C): start at the first candidate (unit batch size) and move
- * to the next larger one while the achievable QPS improves; stop at the first step that does not
- * improve it.  qps[i] = achievable QPS with the i-th candidate batch size.  Returns the index kept. */
+ * to the next larger one until the achievable QPS degrades, i.e. stop at the first step that
+ * lowers it (a step that leaves it unchanged, such as one between two batch sizes that both miss
+ * the latency target, is taken).  qps[i] = achievable QPS with the i-th candidate batch size.
+ * Returns the index kept. */
 int64_t orc_hill_climb(const double* qps, int64_t n_candidates) {
     int64_t i = 0;
-    while (i + 1 < n_candidates && qps[i + 1] > qps[i]) ++i;
+    while (i + 1 < n_candidates && qps[i + 1] >= qps[i]) ++i;
     return i;
 }

@@ -1,0 +1,176 @@
+// Query serving around the model forward: request service times, the single-device FIFO queue,
+// latency-bounded throughput, the batch-size hill climb, and an open-loop trace replay on the GPU.
+//
+// DeepRecSys paper: Section III-C (Poisson arrivals, query sizes), Section IV-A (a query is split
+// into requests of a batch size), Section III-B (throughput is the query rate sustained under a
+// p95 latency target), Section IV-C (the batch size is found by hill climbing on that rate).
+// Everything here is host code except the replay, which drives rec_model_forward.
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <limits>
+#include <vector>
+
+#include "rec_common.h"
+
+namespace {
+
+const double kNaN = std::numeric_limits<double>::quiet_NaN();
+
+// latencies of a FIFO single-server queue, written to lat; returns nothing (sizes checked by callers)
+void fifo(const double* arrival, const double* service, int64_t n, double* lat) {
+    double free_at = 0.0;                      // when the device becomes idle
+    for (int64_t q = 0; q < n; ++q) {
+        const double begin = (q == 0) ? arrival[q] : std::max(arrival[q], free_at);
+        free_at = begin + service[q];
+        lat[q] = free_at - arrival[q];
+    }
+}
+
+double nearest_rank(std::vector<double>& v, double p) {
+    const int64_t n = (int64_t)v.size();
+    int64_t k = (int64_t)std::ceil(p * (double)n) - 1;
+    k = std::min(std::max<int64_t>(k, 0), n - 1);
+    std::nth_element(v.begin(), v.begin() + k, v.end());
+    return v[k];
+}
+
+struct RateTest {
+    const double* unit_arrival;
+    const double* service;
+    int64_t n;
+    double p, sla;
+    std::vector<double> arr, lat;
+    bool operator()(double rate) {
+        for (int64_t i = 0; i < n; ++i) arr[i] = unit_arrival[i] / rate;
+        fifo(arr.data(), service, n, lat.data());
+        return nearest_rank(lat, p) <= sla;    // nth_element reorders lat, which is rewritten next time
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+double rec_sched_query_service(int64_t n, int64_t batch, const double* table) {
+    if (n < 0 || batch < 1 || !table) return kNaN;
+    const int64_t full = n / batch, rest = n % batch;
+    double total = 0.0;
+    for (int64_t k = 0; k < full; ++k) total += table[batch];   // added one by one, in request order
+    if (rest) total += table[rest];
+    return total;
+}
+
+rec_status rec_sched_fifo_latencies(const double* arrival, const double* service, int64_t n, double* latency) {
+    if (n < 0) return REC_ERR_BAD_SHAPE;
+    if (n == 0) return REC_OK;
+    if (!arrival || !service || !latency) return REC_ERR_NULL;
+    for (int64_t i = 1; i < n; ++i)
+        if (arrival[i] < arrival[i - 1]) return REC_ERR_BAD_SHAPE;
+    fifo(arrival, service, n, latency);
+    return REC_OK;
+}
+
+double rec_sched_percentile(const double* x, int64_t n, double p) {
+    if (!x || n < 1 || !(p > 0.0) || p > 1.0) return kNaN;
+    std::vector<double> v(x, x + n);
+    return nearest_rank(v, p);
+}
+
+double rec_sched_max_qps(const double* unit_arrival, const double* service, int64_t n, double p, double sla,
+                         int32_t iters) {
+    if (!unit_arrival || !service || n < 1 || !(p > 0.0) || p > 1.0 || iters < 0) return kNaN;
+    {
+        std::vector<double> s(service, service + n);
+        if (nearest_rank(s, p) > sla) return 0.0;
+    }
+    RateTest ok{unit_arrival, service, n, p, sla, std::vector<double>((size_t)n), std::vector<double>((size_t)n)};
+    double feasible, infeasible;
+    if (ok(1.0)) {
+        feasible = 1.0;
+        infeasible = 2.0;
+        while (infeasible < 1e15 && ok(infeasible)) {
+            feasible = infeasible;
+            infeasible *= 2.0;
+        }
+    } else {
+        infeasible = 1.0;
+        feasible = 0.5;
+        while (feasible > 1e-15 && !ok(feasible)) {
+            infeasible = feasible;
+            feasible *= 0.5;
+        }
+    }
+    for (int32_t k = 0; k < iters; ++k) {
+        const double mid = 0.5 * (feasible + infeasible);
+        if (ok(mid)) feasible = mid;
+        else infeasible = mid;
+    }
+    return feasible;
+}
+
+int64_t rec_sched_hill_climb(const double* qps, int64_t n_candidates) {
+    if (!qps || n_candidates < 1) return -1;
+    int64_t keep = 0;
+    for (int64_t next = 1; next < n_candidates; ++next) {
+        if (qps[next] < qps[keep]) break;       // the rate degrades: stop climbing
+        keep = next;
+    }
+    return keep;
+}
+
+rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, const int64_t* query_first,
+                           const double* arrival_s, int64_t n_queries, float* prob, void* workspace,
+                           size_t workspace_bytes, void* stream, double* latency_s) {
+    if (n_queries < 0) return REC_ERR_BAD_SHAPE;
+    if (n_queries == 0) return REC_OK;
+    if (!m || !requests || !query_first || !arrival_s || !latency_s || !prob) return REC_ERR_NULL;
+    for (int64_t q = 0; q < n_queries; ++q) {
+        if (query_first[q + 1] < query_first[q] || arrival_s[q] < 0.0) return REC_ERR_BAD_SHAPE;
+        if (q > 0 && arrival_s[q] < arrival_s[q - 1]) return REC_ERR_BAD_SHAPE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<hipEvent_t> done((size_t)n_queries + 1, nullptr);
+    auto cleanup = [&]() {
+        for (hipEvent_t e : done)
+            if (e) (void)hipEventDestroy(e);
+    };
+    for (auto& e : done)
+        if (hipEventCreate(&e) != hipSuccess) {
+            cleanup();
+            return REC_ERR_DEVICE;
+        }
+    // time zero: the stream is idle and done[0] has just completed, so device timestamps measured
+    // from done[0] and host time measured from t0 share an origin to within the sync latency
+    if (hipEventRecord(done[0], s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) {
+        cleanup();
+        return REC_ERR_DEVICE;
+    }
+    const auto t0 = std::chrono::steady_clock::now();
+    rec_status st = REC_OK;
+    for (int64_t q = 0; q < n_queries && st == REC_OK; ++q) {
+        while (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < arrival_s[q]) {
+        }
+        for (int64_t r = query_first[q]; r < query_first[q + 1] && st == REC_OK; ++r) {
+            const rec_request& rq = requests[r];
+            st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob, workspace,
+                                   workspace_bytes, stream);
+        }
+        if (st == REC_OK && hipEventRecord(done[(size_t)q + 1], s) != hipSuccess) st = REC_ERR_DEVICE;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess && st == REC_OK) st = REC_ERR_DEVICE;
+    if (st == REC_OK) {
+        for (int64_t q = 0; q < n_queries; ++q) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, done[0], done[(size_t)q + 1]) != hipSuccess) {
+                st = REC_ERR_DEVICE;
+                break;
+            }
+            latency_s[q] = (double)ms * 1e-3 - arrival_s[q];
+        }
+    }
+    cleanup();
+    return st;
+}
+
+}  // extern "C"

@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "librec.so")
-SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("sls.hip", "fc.hip", "fc_fused.hip", "gemm_bf16.hip", "interact.hip", "model.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("sls.hip", "fc.hip", "fc_fused.hip", "gemm_bf16.hip", "interact.hip", "model.hip", "sched.hip")]
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_NEGATIVE_LENGTH, ERR_LENGTHS_MISMATCH, ERR_INDEX_RANGE, \
     ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(9)
@@ -30,6 +30,8 @@ EXPORTS = (
     "rec_mlp_workspace_bytes", "rec_mlp_forward", "rec_f32_to_bf16",
     "rec_interact",
     "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
+    "rec_sched_query_service", "rec_sched_fifo_latencies", "rec_sched_percentile", "rec_sched_max_qps",
+    "rec_sched_hill_climb", "rec_serve_trace",
 )
 
 
@@ -95,6 +97,18 @@ def lib():
     L.rec_model_workspace_bytes.argtypes = [vp, i32]
     L.rec_model_forward.restype = C.c_int
     L.rec_model_forward.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
+    L.rec_sched_query_service.restype = C.c_double
+    L.rec_sched_query_service.argtypes = [i64, i64, vp]
+    L.rec_sched_fifo_latencies.restype = C.c_int
+    L.rec_sched_fifo_latencies.argtypes = [vp, vp, i64, vp]
+    L.rec_sched_percentile.restype = C.c_double
+    L.rec_sched_percentile.argtypes = [vp, i64, C.c_double]
+    L.rec_sched_max_qps.restype = C.c_double
+    L.rec_sched_max_qps.argtypes = [vp, vp, i64, C.c_double, C.c_double, i32]
+    L.rec_sched_hill_climb.restype = i64
+    L.rec_sched_hill_climb.argtypes = [vp, i64]
+    L.rec_serve_trace.restype = C.c_int
+    L.rec_serve_trace.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
     _lib = L
     return L
 
@@ -300,3 +314,62 @@ class Model:
                                      _ptr(prob), _ptr(workspace), workspace.numel(), _stream())
         _check(st, "rec_model_forward")
         return prob
+
+
+# ---- query serving and batch-size tuning (host arrays of float64) ----------------------------
+
+def _host_f64(v):
+    return np.ascontiguousarray(v, dtype=np.float64)
+
+
+def sched_query_service(n: int, batch: int, table) -> float:
+    table = _host_f64(table)
+    assert table.size > batch
+    return lib().rec_sched_query_service(n, batch, table.ctypes.data)
+
+
+def sched_fifo_latencies(arrival, service):
+    arrival, service = _host_f64(arrival), _host_f64(service)
+    lat = np.empty_like(arrival)
+    _check(lib().rec_sched_fifo_latencies(arrival.ctypes.data, service.ctypes.data, arrival.size, lat.ctypes.data),
+           "rec_sched_fifo_latencies")
+    return lat
+
+
+def sched_percentile(x, p: float) -> float:
+    x = _host_f64(x)
+    return lib().rec_sched_percentile(x.ctypes.data, x.size, p)
+
+
+def sched_max_qps(unit_arrival, service, p: float, sla: float, iters: int = 40) -> float:
+    unit_arrival, service = _host_f64(unit_arrival), _host_f64(service)
+    return lib().rec_sched_max_qps(unit_arrival.ctypes.data, service.ctypes.data, service.size, p, sla, iters)
+
+
+def sched_hill_climb(qps) -> int:
+    qps = _host_f64(qps)
+    return lib().rec_sched_hill_climb(qps.ctypes.data, qps.size)
+
+
+class _Request(C.Structure):
+    _fields_ = [("dense", C.c_void_p), ("indices", C.c_void_p), ("n_indices", C.c_int64), ("lengths", C.c_void_p),
+                ("B", C.c_int32)]
+
+
+def serve_trace(model: "Model", queries, arrival_s):
+    """queries: list (one per query) of lists of request objects with .dense .indices .lengths .B
+    (device tensors).  Returns per-query latencies in seconds (NumPy float64)."""
+    flat = [r for q in queries for r in q]
+    reqs = (_Request * max(len(flat), 1))()
+    for i, r in enumerate(flat):
+        reqs[i] = _Request(_ptr(r.dense), _ptr(r.indices), r.indices.numel(), _ptr(r.lengths), r.B)
+    first = _host_i64(np.concatenate([[0], np.cumsum([len(q) for q in queries])]))
+    arrival_s = _host_f64(arrival_s)
+    max_b = max([r.B for r in flat] + [1])
+    prob = torch.empty(max_b, dtype=torch.float32, device=model.device)
+    ws = model.workspace(max_b)
+    lat = np.empty(len(queries), dtype=np.float64)
+    st = lib().rec_serve_trace(model._h, C.addressof(reqs), first.ctypes.data, arrival_s.ctypes.data, len(queries),
+                               _ptr(prob), _ptr(ws), ws.numel(), _stream(), lat.ctypes.data)
+    _check(st, "rec_serve_trace")
+    return lat

@@ -35,8 +35,8 @@ MUTATIONS = {
     "fifo_latency_excludes_wait": ("latency[i] = prev_finish - arrival[i];", "latency[i] = service[i];"),
     "percentile_off_by_one": ("(int64_t)ceil(p * (double)n) - 1;", "(int64_t)ceil(p * (double)n);"),
     "max_qps_returns_infeasible_end": ("    free(lat);\n    return lo;", "    free(lat);\n    return hi;"),
-    "hill_climb_accepts_ties": ("qps[i + 1] > qps[i]", "qps[i + 1] >= qps[i]"),
-    "hill_climb_global_max": ("while (i + 1 < n_candidates && qps[i + 1] > qps[i]) ++i;",
+    "hill_climb_stops_on_ties": ("qps[i + 1] >= qps[i]", "qps[i + 1] > qps[i]"),
+    "hill_climb_global_max": ("while (i + 1 < n_candidates && qps[i + 1] >= qps[i]) ++i;",
                               "for (int64_t j = 1; j < n_candidates; ++j) if (qps[j] > qps[i]) i = j;"),
 }
 

@@ -116,7 +116,9 @@ def test_hill_climb_rule():
     assert oracle.hill_climb([1, 2, 3, 4]) == 3               # keeps improving to the end
     assert oracle.hill_climb([1, 2, 3, 2, 9]) == 2            # stops at the first degradation
     assert oracle.hill_climb([5, 4, 9]) == 0
-    assert oracle.hill_climb([1, 2, 2, 3]) == 1               # a tie is not an improvement
+    assert oracle.hill_climb([1, 2, 2, 3]) == 3               # a tie is not a degradation
+    assert oracle.hill_climb([0, 0, 0, 5, 9, 7]) == 4         # batch sizes that miss the target: keep climbing
+    assert oracle.hill_climb([5, 5, 5]) == 2
     for _ in range(50):                                       # unimodal sequences: the arg max
         q = rng.uniform(size=8)
         peak = rng.integers(0, 8)
