@@ -147,19 +147,21 @@ def interact(vecs):
     return out
 
 
-def model_forward(tables, Wb, bb, Wt, bt, dense, indices, lengths, bf16=False):
-    """Returns (status, prob fp32 [B])."""
+def model_forward(tables, Wb, bb, Wt, bt, dense, indices, lengths, bf16=False, concat=False):
+    """Returns (status, prob fp32 [B]).  concat=True: the concatenating model (Wb may be empty)."""
     tables = [_f32(t) for t in tables]
     T, D = len(tables), tables[0].shape[1]
     rows = np.array([t.shape[0] for t in tables], dtype=np.int64)
     Wb, bb = [_f32(w) for w in Wb], [_f32(b) for b in bb]
     Wt, bt = [_f32(w) for w in Wt], [_f32(b) for b in bt]
-    wb = np.array([Wb[0].shape[1]] + [w.shape[0] for w in Wb], dtype=np.int32)
+    dense = _f32(dense)
+    wb = np.array([Wb[0].shape[1] if Wb else dense.shape[1]] + [w.shape[0] for w in Wb], dtype=np.int32)
     wt = np.array([Wt[0].shape[1]] + [w.shape[0] for w in Wt], dtype=np.int32)
     dense, indices, lengths = _f32(dense), _i32(indices), _i32(lengths)
     B = dense.shape[0]
     prob = np.zeros(B, dtype=np.float32)
-    st = lib().orc_model_forward(
+    fn = lib().orc_model_forward_concat if concat else lib().orc_model_forward
+    st = fn(
         _ptr_array(tables), _p(rows), C.c_int32(T), C.c_int32(D),
         _ptr_array(Wb), _ptr_array(bb), _p(wb), C.c_int32(len(Wb)),
         _ptr_array(Wt), _ptr_array(bt), _p(wt), C.c_int32(len(Wt)),

@@ -241,6 +241,41 @@ int orc_model_forward(const float* const* tables, const int64_t* rows, int32_t T
     return ORC_OK;
 }
 
+/* Concatenating models (Table I: NCF, Wide&Deep use "Concat" where DLRM interacts; Section II-A:
+ * dense features that bypass the Dense-FC stack are joined directly with the embedding outputs).
+ * Predictor input of sample b = [ x_b | E[b][0][:] | ... | E[b][T-1][:] ], where x_b is the output
+ * of the dense stack (ReLU on every layer), or the dense features themselves when that stack has
+ * no layers (nb == 0, wb[0] = number of dense features), and E is the pooled embedding of each
+ * table (one lookup per bag in the paper's concat models; any bag length is summed).  Top stack
+ * as in orc_model_forward.  wt[0] must equal wb[nb] + T*D. */
+int orc_model_forward_concat(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                             const float* const* Wb, const float* const* bb, const int32_t* wb, int32_t nb,
+                             const float* const* Wt, const float* const* bt, const int32_t* wt, int32_t nt,
+                             int32_t bf16_operands, const float* dense, const int32_t* indices,
+                             int64_t n_indices, const int32_t* lengths, int32_t B, float* prob) {
+    const int32_t X = wb[nb];
+    if (wt[0] != X + T * D || wt[nt] != 1) return ORC_ERR_BAD_SHAPE;
+    int64_t n_bad, first_bad;
+    int st = orc_validate(rows, T, indices, n_indices, lengths, B, &n_bad, &first_bad);
+    if (st != ORC_OK) return st;
+    if (B == 0) return ORC_OK;
+    const int64_t Wc = wt[0];
+    int64_t* off = (int64_t*)malloc(sizeof(int64_t) * ((size_t)T * B + 1));
+    float* cat = (float*)malloc(sizeof(float) * (size_t)B * Wc);
+    orc_offsets(lengths, (int64_t)T * B, off);
+    orc_sls(tables, T, D, indices, off, B, cat + X, Wc, D, NULL, NULL);
+    if (nb > 0) {
+        orc_mlp(Wb, bb, wb, nb, bf16_operands, ORC_ACT_RELU, ORC_ACT_RELU, dense, wb[0], cat, Wc, B);
+    } else {
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t f = 0; f < X; ++f) cat[b * Wc + f] = dense[(int64_t)b * X + f];
+    }
+    orc_mlp(Wt, bt, wt, nt, bf16_operands, ORC_ACT_RELU, ORC_ACT_SIGMOID, cat, Wc, prob, 1, B);
+    free(off);
+    free(cat);
+    return ORC_OK;
+}
+
 /* Split a query of n items into consecutive sub-batches of size Bsz (Section
  * IV-A: a query is divided into requests of a given batch size): floor(n/Bsz)
  * full ones, then one of n mod Bsz if that is non-zero.  Writes (start, count)

@@ -35,6 +35,13 @@ MUTATIONS = {
     "fifo_latency_excludes_wait": ("latency[i] = prev_finish - arrival[i];", "latency[i] = service[i];"),
     "percentile_off_by_one": ("(int64_t)ceil(p * (double)n) - 1;", "(int64_t)ceil(p * (double)n);"),
     "max_qps_returns_infeasible_end": ("    free(lat);\n    return lo;", "    free(lat);\n    return hi;"),
+    "concat_embeddings_overwrite_dense": ("orc_sls(tables, T, D, indices, off, B, cat + X, Wc, D, NULL, NULL);",
+                                          "orc_sls(tables, T, D, indices, off, B, cat, Wc, D, NULL, NULL);"),
+    "concat_table_stride": ("orc_sls(tables, T, D, indices, off, B, cat + X, Wc, D, NULL, NULL);",
+                            "orc_sls(tables, T, D, indices, off, B, cat + X, Wc, 1, NULL, NULL);"),
+    "concat_dense_dropped": ("cat[b * Wc + f] = dense[(int64_t)b * X + f];", "cat[b * Wc + f] = 0.0f;"),
+    "concat_dense_transposed": ("cat[b * Wc + f] = dense[(int64_t)b * X + f];",
+                                "cat[b * Wc + f] = dense[((int64_t)f * B + b) % ((int64_t)B * X)];"),
     "hill_climb_stops_on_ties": ("qps[i + 1] >= qps[i]", "qps[i + 1] > qps[i]"),
     "hill_climb_global_max": ("while (i + 1 < n_candidates && qps[i + 1] >= qps[i]) ++i;",
                               "for (int64_t j = 1; j < n_candidates; ++j) if (qps[j] > qps[i]) i = j;"),

@@ -401,3 +401,78 @@ def test_oracle_threads_do_not_change_results():
     p4 = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, dense, idx, lengths)[1]
     oracle.set_threads(1)
     assert np.array_equal(p1, p4)
+
+
+# ---- concatenating models (Table I: NCF / Wide&Deep rows) --------------------------------
+
+def test_concat_model_hand_example(golden):
+    g = golden("concat_model_hand_example.txt")
+    D, B = int(g["D"][0]), int(g["B"][0])
+    tables = [np.array(g[f"table{t}"], np.float32).reshape(-1, D) for t in range(2)]
+    dense = np.array(g["dense"], np.float32).reshape(B, 2)
+    Wt = [np.array(g["Wt0"], np.float32).reshape(2, 6), np.array(g["Wt1"], np.float32).reshape(1, 2)]
+    bt = [np.array(g["bt0"], np.float32), np.array(g["bt1"], np.float32)]
+    lengths, idx = np.array(g["lengths"], np.int32), np.array(g["indices"], np.int32)
+    E = oracle.sls(tables, idx, lengths, B)
+    cat = np.concatenate([dense, E.reshape(B, -1)], axis=1)
+    assert cat.reshape(-1).tolist() == g["cat"]
+    h = oracle.fc(cat, Wt[0], bt[0], oracle.ACT_RELU)
+    assert h.reshape(-1).tolist() == g["hidden"]
+    st, p = oracle.model_forward(tables, [], [], Wt, bt, dense, idx, lengths, concat=True)
+    assert st == oracle.OK
+    assert np.allclose(p, g["prob"], rtol=1e-7, atol=0)
+
+
+@pytest.mark.parametrize("with_dense_stack", [False, True])
+def test_concat_model_vs_torch_cpu_float64(with_dense_stack):
+    import torch
+    T, R, D, F, B = 5, 40, 4, 6, 11
+    tables = [rng.normal(size=(R, D)).astype(np.float32) for _ in range(T)]
+    X = 8 if with_dense_stack else F
+    pb = synth.mlp_params((F, 10, X), 0, 5) if with_dense_stack else synth.mlp_params((F,), 0, 5)
+    pt = synth.mlp_params((X + T * D, 16, 8, 1), 1, 5)
+    dense = rng.normal(size=(B, F)).astype(np.float32)
+    idx, lengths = _bags(T, B, R, 1, 1)                         # one lookup per table, as in Table I
+    if with_dense_stack:
+        idx, lengths = _bags(T, B, R, 0, 5)                     # pooled sums are concatenated just the same
+    st, p = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, dense, idx, lengths, concat=True)
+    assert st == oracle.OK
+    # independent formulation: float64 torch ops, rounding to fp32 between layers as the oracle does
+    x = torch.from_numpy(dense).double()
+    for W, b in zip(pb.W, pb.b):
+        x = torch.relu(torch.nn.functional.linear(x, torch.from_numpy(W).double(), torch.from_numpy(b).double())).float().double()
+    off = np.concatenate([[0], np.cumsum(lengths)])[:-1].reshape(T, B)
+    parts = [x]
+    for t in range(T):
+        lo, hi = off[t, 0], off[t, 0] + lengths.reshape(T, B)[t].sum()
+        e = torch.nn.functional.embedding_bag(torch.from_numpy(idx[lo:hi].astype(np.int64)), torch.from_numpy(tables[t]).double(),
+                                              torch.from_numpy((off[t] - off[t, 0]).astype(np.int64)), mode="sum")
+        parts.append(e.float().double())
+    z = torch.cat(parts, dim=1)
+    for i, (W, b) in enumerate(zip(pt.W, pt.b)):
+        z = torch.nn.functional.linear(z, torch.from_numpy(W).double(), torch.from_numpy(b).double())
+        z = (torch.sigmoid(z) if i == len(pt.W) - 1 else torch.relu(z)).float().double()
+    assert np.allclose(p, z.reshape(-1).numpy(), rtol=2e-6, atol=1e-7)
+
+
+def test_concat_model_shape_errors_and_column_blocks():
+    T, R, D, F, B = 3, 20, 4, 4, 6
+    tables = [rng.normal(size=(R, D)).astype(np.float32) for _ in range(T)]
+    pt = synth.mlp_params((F + T * D, 8, 1), 1, 9)
+    dense = rng.normal(size=(B, F)).astype(np.float32)
+    idx, lengths = _bags(T, B, R, 1, 1)
+    st, p = oracle.model_forward(tables, [], [], pt.W, pt.b, dense, idx, lengths, concat=True)
+    assert st == oracle.OK
+    # a predictor that ignores the columns of table 1 does not see table 1's indices ...
+    W0 = pt.W[0].copy()
+    W0[:, F + D:F + 2 * D] = 0
+    idx2 = idx.copy()
+    idx2[B:2 * B] = (idx2[B:2 * B] + 7) % R
+    pa = oracle.model_forward(tables, [], [], [W0] + pt.W[1:], pt.b, dense, idx, lengths, concat=True)[1]
+    pb_ = oracle.model_forward(tables, [], [], [W0] + pt.W[1:], pt.b, dense, idx2, lengths, concat=True)[1]
+    assert np.array_equal(pa, pb_)
+    # ... and the full predictor does
+    assert not np.array_equal(p, oracle.model_forward(tables, [], [], pt.W, pt.b, dense, idx2, lengths, concat=True)[1])
+    # predictor input width must be dense width + T*D
+    bad = synth.mlp_params((F + T * D + 1, 8, 1), 1, 9)
+    assert oracle.model_forward(tables, [], [], bad.W, bad.b, dense, idx, lengths, concat=True)[0] == oracle.ERR_BAD_SHAPE
