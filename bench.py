@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="rmc2", choices=["tiny", "rmc1", "rmc2", "rmc2-uniform", "rmc3"])
+    ap.add_argument("--workload", default="rmc2", choices=["tiny", "rmc1", "rmc2", "rmc2-uniform", "rmc3", "wnd"])
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-batch-size", action="store_true",
@@ -85,7 +85,7 @@ def cpu_baseline(cfg, batch):
 
     def oracle_forward(cfg, tables, batch, indices):
         st, p = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, batch.dense, indices, batch.lengths,
-                                     bf16=cfg.bf16)
+                                     bf16=cfg.bf16, concat=cfg.interaction == "concat")
         assert st == oracle.OK
         return p
 
@@ -159,13 +159,18 @@ def main():
         # MLP-dominated workload: the dominant kernel is the first (widest) Dense-FC layer, a bf16
         # MFMA contraction [B x F] . [n1 x F]^T.  Timed alone between events: the layer call launches
         # the tiled GEMM and, when k is split across blocks, the small kernel that folds the partials.
-        W0, b0 = model.bottom_W[0], model.bottom_b[0]
+        # (a model without a dense stack: the first predictor layer, fed a resident random input)
+        if model.bottom_W:
+            W0, b0, xs = model.bottom_W[0], model.bottom_b[0], [d.dense for d in dbs]
+        else:
+            W0, b0 = model.top_W[0], model.top_b[0]
+            xs = [torch.randn((cfg.B, W0.shape[1]), dtype=torch.float32, device="cuda")]
         n1, F = W0.shape
         y1 = torch.empty((cfg.B, n1), dtype=torch.float32, device="cuda")
         ws1 = torch.empty(max(256, rec.mlp_workspace_bytes([F, n1], cfg.B, rec.BF16)), dtype=torch.uint8, device="cuda")
 
         def layer1(i):
-            rec.mlp_forward([W0], [b0], dbs[i % len(dbs)].dense, rec.ACT_RELU, rec.ACT_RELU, wdtype=rec.BF16, y=y1,
+            rec.mlp_forward([W0], [b0], xs[i % len(xs)], rec.ACT_RELU, rec.ACT_RELU, wdtype=rec.BF16, y=y1,
                             ldy=n1, workspace=ws1)
 
         l1_sec = event_time(layer1, a.steps, a.warmup, torch)
@@ -197,7 +202,8 @@ def main():
            "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
            "config": {"workload": f"{cfg.name}-shaped DLRM forward", "batch": cfg.B, "tables": cfg.T, "rows": cfg.R,
                       "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
-                      "bottom": list(cfg.bottom), "top": list(cfg.top), "distinct_batches": len(dbs)},
+                      "bottom": list(cfg.bottom), "top": list(cfg.top), "interaction": cfg.interaction,
+                      "distinct_batches": len(dbs)},
            "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "setup_s": setup_s}
     if roofline is not sls_roofline:
         out["sls_roofline"] = sls_roofline

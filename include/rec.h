@@ -148,11 +148,18 @@ rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int32_t D,
                         float* out, int64_t ldo, void* stream);
 
 /* ---- whole model (Figure 2) ------------------------------------------------
- * offsets -> SLS into slots 1..T of [B][T+1][D]; bottom stack (ReLU after every
- * layer) into slot 0; interaction; top stack (ReLU on hidden layers, sigmoid on
- * the 1-wide last layer) -> one probability per sample.
+ * REC_INTERACT_DOT (the DLRM rows of Table I): offsets -> SLS into slots 1..T of
+ * [B][T+1][D]; bottom stack (ReLU after every layer) into slot 0; interaction; top
+ * stack (ReLU on hidden layers, sigmoid on the 1-wide last layer) -> one probability
+ * per sample.
+ * REC_INTERACT_CONCAT (the "Concat" rows of Table I, NCF / Wide&Deep; Section II-A):
+ * the top stack's input is [ x | E_0 | ... | E_{T-1} ], x = bottom stack output, or the
+ * dense features themselves when n_bottom = 0 (bottom_widths = {F}, bottom_W/b unused);
+ * E_t = pooled embedding of table t.  x's width must be a multiple of 4.
  * The handle BORROWS every pointer in the descriptor: DEV memory must stay
  * alive and unchanged while the handle is used; HOST arrays are copied. */
+typedef enum { REC_INTERACT_DOT = 0, REC_INTERACT_CONCAT = 1 } rec_interaction;
+
 typedef struct {
     int32_t T;                       /* embedding tables, 1 <= T <= 127 */
     int32_t D;                       /* embedding dim = bottom stack output width */
@@ -167,6 +174,8 @@ typedef struct {
     const void* const* top_W;
     const float* const* top_b;
     rec_dtype mlp_dtype;             /* REC_F32 or REC_BF16, both stacks */
+    rec_interaction interaction;     /* REC_INTERACT_DOT: bottom_widths last = D, top_widths[0] = D + T(T+1)/2;
+                                        REC_INTERACT_CONCAT: top_widths[0] = bottom_widths last + T*D */
 } rec_model_desc;
 
 typedef struct rec_model rec_model;

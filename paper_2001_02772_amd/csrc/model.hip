@@ -1,6 +1,7 @@
 // Whole-model forward (Figure 2 of the DeepRecSys paper): embedding bags and the
 // dense stack feed the interaction, the predictor stack ends in a sigmoid.
 // Also the host-side query splitter of Section IV-A and the status names.
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -14,7 +15,8 @@ struct rec_model {
     std::vector<const void*> bottom_W, top_W;
     std::vector<const float*> bottom_b, top_b;
     rec_dtype dt;
-    int64_t ld_inter;        // row stride of the interaction output
+    bool concat;             // predictor input = [bottom output | pooled embeddings]
+    int64_t ld_inter;        // row stride of the interaction output (dot) or of the joined row (concat)
 };
 
 namespace {
@@ -37,16 +39,27 @@ ModelWorkspace carve(const rec_model* m, int32_t B, void* base) {
     w.sls_bytes = rec_sls_workspace_bytes(m->T, B);
     p += w.sls_bytes;
     w.vecs = reinterpret_cast<float*>(p);
-    p += rec_round_up((size_t)B * V * m->D * sizeof(float), 256);
+    if (!m->concat) p += rec_round_up((size_t)B * V * m->D * sizeof(float), 256);
     w.inter = reinterpret_cast<float*>(p);
     p += rec_round_up((size_t)B * m->ld_inter * sizeof(float), 256);
     w.mlp = p;
-    const size_t a = rec_mlp_workspace_bytes(m->bottom_widths.data(), (int32_t)m->bottom_W.size(), B, m->dt);
+    const size_t a = m->bottom_W.empty() ? 0 : rec_mlp_workspace_bytes(m->bottom_widths.data(), (int32_t)m->bottom_W.size(), B, m->dt);
     const size_t c = rec_mlp_workspace_bytes(m->top_widths.data(), (int32_t)m->top_W.size(), B, m->dt);
     w.mlp_bytes = a > c ? a : c;
     p += w.mlp_bytes;
     w.total = (size_t)(p - static_cast<char*>(base));
     return w;
+}
+
+// dst[b][0..F) = src[b][0..F): dense features that skip the dense stack (Section II-A, Wide&Deep)
+__global__ __launch_bounds__(256) void copy_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                        int32_t B, int32_t F, int64_t ld_dst) {
+    const int64_t n4 = (int64_t)B * (F / 4);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const int64_t b = i / (F / 4);
+        const int32_t c = (int32_t)(i - b * (F / 4)) * 4;
+        *reinterpret_cast<float4*>(dst + b * ld_dst + c) = *reinterpret_cast<const float4*>(src + b * F + c);
+    }
 }
 
 }  // namespace
@@ -85,10 +98,11 @@ int64_t rec_split_query(int64_t n, int64_t batch, int64_t* start, int64_t* count
 rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     if (!d || !out) return REC_ERR_NULL;
     *out = nullptr;
-    if (!d->tables || !d->rows || !d->bottom_widths || !d->bottom_W || !d->bottom_b || !d->top_widths || !d->top_W ||
-        !d->top_b)
-        return REC_ERR_NULL;
-    if (d->T < 1 || d->n_bottom < 1 || d->n_top < 1) return REC_ERR_BAD_SHAPE;
+    if (!d->tables || !d->rows || !d->bottom_widths || !d->top_widths || !d->top_W || !d->top_b) return REC_ERR_NULL;
+    if (d->n_bottom > 0 && (!d->bottom_W || !d->bottom_b)) return REC_ERR_NULL;
+    if (d->interaction != REC_INTERACT_DOT && d->interaction != REC_INTERACT_CONCAT) return REC_ERR_UNSUPPORTED;
+    const bool concat = d->interaction == REC_INTERACT_CONCAT;
+    if (d->T < 1 || d->n_bottom < (concat ? 0 : 1) || d->n_top < 1) return REC_ERR_BAD_SHAPE;
     if (d->T > 127 || d->D < 4 || d->D > 256 || d->D % 4) return REC_ERR_UNSUPPORTED;
     if (d->mlp_dtype != REC_F32 && d->mlp_dtype != REC_BF16) return REC_ERR_UNSUPPORTED;
     for (int32_t l = 0; l <= d->n_bottom; ++l)
@@ -96,8 +110,14 @@ rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     for (int32_t l = 0; l <= d->n_top; ++l)
         if (d->top_widths[l] < 1) return REC_ERR_BAD_SHAPE;
     const int32_t V = d->T + 1;
-    if (d->bottom_widths[d->n_bottom] != d->D) return REC_ERR_BAD_SHAPE;
-    if (d->top_widths[0] != d->D + V * (V - 1) / 2 || d->top_widths[d->n_top] != 1) return REC_ERR_BAD_SHAPE;
+    const int32_t X = d->bottom_widths[d->n_bottom];
+    if (concat) {
+        if ((int64_t)d->top_widths[0] != (int64_t)X + (int64_t)d->T * d->D || d->top_widths[d->n_top] != 1) return REC_ERR_BAD_SHAPE;
+        if (X % 4) return REC_ERR_UNSUPPORTED;
+    } else {
+        if (X != d->D) return REC_ERR_BAD_SHAPE;
+        if (d->top_widths[0] != d->D + V * (V - 1) / 2 || d->top_widths[d->n_top] != 1) return REC_ERR_BAD_SHAPE;
+    }
     for (int32_t t = 0; t < d->T; ++t) {
         if (d->rows[t] < 1) return REC_ERR_BAD_SHAPE;
         if (d->rows[t] > 2147483647LL) return REC_ERR_UNSUPPORTED;
@@ -114,11 +134,14 @@ rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     m->rows.assign(d->rows, d->rows + d->T);
     m->bottom_widths.assign(d->bottom_widths, d->bottom_widths + d->n_bottom + 1);
     m->top_widths.assign(d->top_widths, d->top_widths + d->n_top + 1);
-    m->bottom_W.assign(d->bottom_W, d->bottom_W + d->n_bottom);
-    m->bottom_b.assign(d->bottom_b, d->bottom_b + d->n_bottom);
+    if (d->n_bottom > 0) {
+        m->bottom_W.assign(d->bottom_W, d->bottom_W + d->n_bottom);
+        m->bottom_b.assign(d->bottom_b, d->bottom_b + d->n_bottom);
+    }
     m->top_W.assign(d->top_W, d->top_W + d->n_top);
     m->top_b.assign(d->top_b, d->top_b + d->n_top);
     m->dt = d->mlp_dtype;
+    m->concat = concat;
     m->ld_inter = (d->top_widths[0] + 3) / 4 * 4;
     *out = m;
     return REC_OK;
@@ -142,6 +165,30 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
     const ModelWorkspace w = carve(m, B, workspace);
     if (workspace_bytes < w.total) return REC_ERR_WORKSPACE;
     const int32_t V = m->T + 1, D = m->D;
+
+    if (m->concat) {
+        // [ x | E_0 .. E_{T-1} ] is assembled in place: the pooling kernel and the dense stack (or
+        // the copy of the dense features) write their columns of the joined rows directly
+        const int32_t X = m->bottom_widths.back();
+        const int64_t ldc = m->ld_inter;
+        rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X, ldc,
+                                        D, w.sls, w.sls_bytes, stream);
+        if (st != REC_OK) return st;
+        if (m->bottom_W.empty()) {
+            const int64_t n4 = (int64_t)B * (X / 4);
+            const unsigned blocks = (unsigned)std::min<int64_t>((n4 + 255) / 256, 4096);
+            hipLaunchKernelGGL(copy_rows_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), dense, w.inter,
+                               B, X, ldc);
+            REC_CHECK_LAUNCH();
+        } else {
+            st = rec_mlp_forward(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(),
+                                 (int32_t)m->bottom_W.size(), m->dt, REC_ACT_RELU, REC_ACT_RELU, dense, m->bottom_widths[0],
+                                 w.inter, ldc, B, w.mlp, w.mlp_bytes, stream);
+            if (st != REC_OK) return st;
+        }
+        return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths.data(), (int32_t)m->top_W.size(), m->dt,
+                               REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, ldc, prob, 1, B, w.mlp, w.mlp_bytes, stream);
+    }
 
     rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
                                     (int64_t)V * D, D, w.sls, w.sls_bytes, stream);

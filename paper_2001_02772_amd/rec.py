@@ -23,6 +23,7 @@ OK, ERR_NULL, ERR_BAD_SHAPE, ERR_NEGATIVE_LENGTH, ERR_LENGTHS_MISMATCH, ERR_INDE
     ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_DEVICE = range(9)
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_SIGMOID = 0, 1, 2
+INTERACT_DOT, INTERACT_CONCAT = 0, 1
 
 EXPORTS = (
     "rec_status_string", "rec_split_query",
@@ -267,23 +268,26 @@ class _ModelDesc(C.Structure):
                 ("n_bottom", C.c_int32), ("bottom_widths", C.c_void_p), ("bottom_W", C.c_void_p),
                 ("bottom_b", C.c_void_p),
                 ("n_top", C.c_int32), ("top_widths", C.c_void_p), ("top_W", C.c_void_p), ("top_b", C.c_void_p),
-                ("mlp_dtype", C.c_int)]
+                ("mlp_dtype", C.c_int), ("interaction", C.c_int)]
 
 
 class Model:
     """Owns the device tensors of one model and the library handle that borrows them."""
 
-    def __init__(self, tables: Tables, bottom_W, bottom_b, top_W, top_b, wdtype=F32):
-        self.tables, self.wdtype = tables, wdtype
+    def __init__(self, tables: Tables, bottom_W, bottom_b, top_W, top_b, wdtype=F32, interaction=INTERACT_DOT,
+                 dense_features: int | None = None):
+        """interaction=INTERACT_CONCAT allows an empty bottom stack; then pass dense_features = F."""
+        self.tables, self.wdtype, self.interaction = tables, wdtype, interaction
         self.bottom_W, self.bottom_b, self.top_W, self.top_b = list(bottom_W), list(bottom_b), list(top_W), list(top_b)
-        self.bottom_widths = _host_i32([bottom_W[0].shape[1]] + [w.shape[0] for w in bottom_W])
+        self.bottom_widths = _host_i32([bottom_W[0].shape[1] if self.bottom_W else dense_features]
+                                       + [w.shape[0] for w in bottom_W])
         self.top_widths = _host_i32([top_W[0].shape[1]] + [w.shape[0] for w in top_W])
         self.device = tables.ptrs.device
         arrays = [_ptr_array_host(a) for a in (self.bottom_W, self.bottom_b, self.top_W, self.top_b)]
         d = _ModelDesc(tables.T, tables.D, _ptr(tables.ptrs), tables.rows.ctypes.data,
                        len(self.bottom_W), self.bottom_widths.ctypes.data, C.addressof(arrays[0]), C.addressof(arrays[1]),
                        len(self.top_W), self.top_widths.ctypes.data, C.addressof(arrays[2]), C.addressof(arrays[3]),
-                       wdtype)
+                       wdtype, interaction)
         h = C.c_void_p(0)
         _check(lib().rec_model_create(C.addressof(d), C.addressof(h)), "rec_model_create")
         self._h = h

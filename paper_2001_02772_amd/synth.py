@@ -156,6 +156,7 @@ class Config:
     top: tuple             # layer widths, top[0] == D + V(V-1)/2, top[-1] == 1
     bf16: bool = False     # MLP operands rounded to bf16 (fp32 accumulate)
     zipf_alpha: float = 1.05
+    interaction: str = "dot"   # "dot": pairwise dots (DLRM); "concat": top input = [bottom output | embeddings]
 
     @property
     def V(self) -> int:
@@ -182,6 +183,12 @@ CONFIGS = {
                            "uniform01", (13, 256, 128, 64), (884, 512, 128, 1)),
     "rmc3": Config("rmc3", 1024, 2560, 10, 1_000_000, 32, 10, 30, "uniform", "normal",
                    (2560, 1024, 256, 32), (87, 512, 256, 1), bf16=True),
+    # Wide&Deep-shaped (Table I): no dense stack, ~1000 dense features joined with one lookup from each of
+    # tens of tables, predictor 1024-512-256 and a 1-wide output
+    "wnd": Config("wnd", 1024, 1024, 32, 500_000, 32, 1, 1, "zipf", "normal",
+                  (1024,), (2048, 1024, 512, 256, 1), bf16=True, interaction="concat"),
+    "wnd-tiny": Config("wnd-tiny", 48, 16, 5, 5_000, 8, 1, 1, "uniform", "normal",
+                       (16,), (56, 32, 16, 1), interaction="concat"),
 }
 
 # the query-size sweep runs on the rmc2 model
@@ -190,8 +197,11 @@ SWEEP_QUERIES = 2000
 
 
 def check_config(c: Config) -> None:
-    assert c.bottom[0] == c.F and c.bottom[-1] == c.D
-    assert c.top[0] == c.D + c.P and c.top[-1] == 1
+    assert c.bottom[0] == c.F and c.top[-1] == 1
+    if c.interaction == "concat":
+        assert c.top[0] == c.bottom[-1] + c.T * c.D
+    else:
+        assert c.interaction == "dot" and c.bottom[-1] == c.D and c.top[0] == c.D + c.P
 
 
 for _c in CONFIGS.values():

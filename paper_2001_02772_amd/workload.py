@@ -25,7 +25,9 @@ def device_model(cfg: synth.Config, device="cuda", seed: int = synth.MASTER_SEED
     tables = tables if tables is not None else device_tables(cfg, device, seed)
     Wb, bb = device_mlp(synth.mlp_params(cfg.bottom, 0, seed), cfg.bf16, device)
     Wt, bt = device_mlp(synth.mlp_params(cfg.top, 1, seed), cfg.bf16, device)
-    return rec.Model(tables, Wb, bb, Wt, bt, rec.BF16 if cfg.bf16 else rec.F32)
+    return rec.Model(tables, Wb, bb, Wt, bt, rec.BF16 if cfg.bf16 else rec.F32,
+                     interaction=rec.INTERACT_CONCAT if cfg.interaction == "concat" else rec.INTERACT_DOT,
+                     dense_features=cfg.F)
 
 
 class DeviceBatch:

@@ -36,6 +36,7 @@ def compact_tables(cfg, batch, seed=synth.MASTER_SEED):
 def oracle_forward(cfg, tables, batch, indices=None, seed=synth.MASTER_SEED):
     pb, pt = synth.mlp_params(cfg.bottom, 0, seed), synth.mlp_params(cfg.top, 1, seed)
     st, p = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, batch.dense,
-                                 batch.indices if indices is None else indices, batch.lengths, bf16=cfg.bf16)
+                                 batch.indices if indices is None else indices, batch.lengths, bf16=cfg.bf16,
+                                 concat=cfg.interaction == "concat")
     assert st == oracle.OK
     return p

@@ -20,7 +20,7 @@ def rec():
     return _rec
 
 
-@pytest.mark.parametrize("name", ["rmc1", "rmc2", "rmc2-uniform", "rmc3"])
+@pytest.mark.parametrize("name", ["rmc1", "rmc2", "rmc2-uniform", "rmc3", "wnd"])
 def test_full_size_model_and_sls(rec, name):
     import oracle
     from paper_2001_02772_amd import workload

@@ -246,6 +246,55 @@ def test_model_forward_small(rec, name, R, B):
     assert np.array_equal(got, model.forward(db.dense, db.indices, db.lengths, B).cpu().numpy())
 
 
+CONCAT_VARIANTS = {
+    "wnd-tiny": synth.CONFIGS["wnd-tiny"],
+    "wnd-small-bf16": synth.CONFIGS["wnd"].replace(R=3000, B=70),
+    "wnd-tiny-bf16": synth.CONFIGS["wnd-tiny"].replace(bf16=True),
+    # a dense stack in front of the join, several lookups per bag (pooled sums are joined)
+    "concat-with-dense-stack": synth.CONFIGS["wnd-tiny"].replace(bottom=(16, 24, 12), top=(12 + 5 * 8, 32, 1), len_lo=0,
+                                                                 len_hi=6, B=37),
+    # wide join: the first predictor layer takes the tiled kernel's split-k path
+    "concat-wide": synth.CONFIGS["wnd-tiny"].replace(F=256, bottom=(256,), T=12, D=64, top=(256 + 12 * 64, 128, 1), B=200),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CONCAT_VARIANTS))
+def test_concat_model_forward_small(rec, name):
+    from paper_2001_02772_amd import workload
+    cfg = CONCAT_VARIANTS[name]
+    synth.check_config(cfg)
+    tables = _host_model(cfg)
+    model = workload.device_model(cfg, tables=rec.Tables([dev(t) for t in tables]))
+    batch = synth.BatchGenerator(cfg).batch(3)
+    db = workload.DeviceBatch(batch)
+    got = model.forward(db.dense, db.indices, db.lengths, cfg.B).cpu().numpy()
+    want = oracle_forward(cfg, tables, batch)
+    assert np.all((got >= 0) & (got <= 1))
+    assert_close(got, want, TOL_BF16 if cfg.bf16 else TOL_F32, f"concat model {name}")
+    pieces = []
+    for start, count in rec.split_query(cfg.B, 16):
+        sb = workload.DeviceBatch(workload.slice_batch(batch, cfg.T, start, count))
+        pieces.append(model.forward(sb.dense, sb.indices, sb.lengths, count).cpu().numpy())
+    assert_close(np.concatenate(pieces), want, TOL_BF16 if cfg.bf16 else TOL_F32, f"split concat model {name}")
+
+
+def test_concat_model_create_errors(rec):
+    cfg = synth.CONFIGS["wnd-tiny"]
+    tables = rec.Tables([dev(t) for t in _host_model(cfg)])
+    from paper_2001_02772_amd import workload
+    Wt, bt = workload.device_mlp(synth.mlp_params((57, 8, 1), 1), False)
+    with pytest.raises(rec.RecError) as e:                         # predictor input != F + T*D
+        rec.Model(tables, [], [], Wt, bt, interaction=rec.INTERACT_CONCAT, dense_features=16)
+    assert e.value.status == rec.ERR_BAD_SHAPE
+    Wt, bt = workload.device_mlp(synth.mlp_params((55, 8, 1), 1), False)
+    with pytest.raises(rec.RecError) as e:                         # joined dense part not a multiple of 4 wide
+        rec.Model(tables, [], [], Wt, bt, interaction=rec.INTERACT_CONCAT, dense_features=15)
+    assert e.value.status == rec.ERR_UNSUPPORTED
+    with pytest.raises(rec.RecError) as e:                         # the dot interaction needs a dense stack
+        rec.Model(tables, [], [], Wt, bt, interaction=rec.INTERACT_DOT, dense_features=16)
+    assert e.value.status == rec.ERR_BAD_SHAPE
+
+
 def test_model_edge_cases(rec):
     from paper_2001_02772_amd import workload
     cfg = synth.CONFIGS["tiny"].replace(R=100)
