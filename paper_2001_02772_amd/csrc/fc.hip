@@ -356,6 +356,16 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
                            int32_t n_layers, rec_dtype wdtype, rec_act hidden_act, rec_act final_act,
                            const float* x, int64_t ldx, float* y, int64_t ldy, int32_t B, void* workspace,
                            size_t workspace_bytes, void* stream) {
+    return rec_mlp_forward_scan(W, bias, widths, n_layers, wdtype, hidden_act, final_act, x, ldx, y, ldy, B, workspace,
+                                workspace_bytes, stream, nullptr);
+}
+
+}  // extern "C"
+
+rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, const int32_t* widths, int32_t n_layers,
+                                rec_dtype wdtype, rec_act hidden_act, rec_act final_act, const float* x, int64_t ldx,
+                                float* y, int64_t ldy, int32_t B, void* workspace, size_t workspace_bytes, void* stream,
+                                const rec_scan_job* scan) {
     if (!W || !bias || !widths) return REC_ERR_NULL;
     if (n_layers < 1 || B < 0) return REC_ERR_BAD_SHAPE;
     if (wdtype != REC_F32 && wdtype != REC_BF16) return REC_ERR_UNSUPPORTED;
@@ -407,8 +417,19 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
             a.y_bf16 = bf && !last;
             a.ldy = ldd;
             a.B = B;
-            st = rec_fused_mlp_launch(a, wdtype, s);
+            if (scan && rec_scan_parallel_tiles(scan->n) < 1) {
+                st = rec_scan_launch(*scan, s);
+                if (st != REC_OK) return st;
+                scan = nullptr;
+            }
+            st = rec_fused_mlp_launch(a, wdtype, scan, s);
+            scan = nullptr;
         } else {
+            if (scan) {
+                st = rec_scan_launch(*scan, s);
+                if (st != REC_OK) return st;
+                scan = nullptr;
+            }
             st = launch_layer(cur, cur_bf16, ld, W[l], wdtype, bias[l], B, widths[l], widths[l + 1],
                               last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, partial, s);
         }
@@ -421,6 +442,8 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
     }
     return REC_OK;
 }
+
+extern "C" {
 
 rec_status rec_f32_to_bf16(const float* src, uint16_t* dst, int64_t n, void* stream) {
     if (n < 0) return REC_ERR_BAD_SHAPE;

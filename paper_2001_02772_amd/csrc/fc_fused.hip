@@ -10,6 +10,7 @@
 // them once), and only the last layer's output goes back to memory.
 // fp32: v_mfma_f32_16x16x4_f32;  bf16 operands: v_mfma_f32_16x16x32_bf16.
 #include "rec_common.h"
+#include "scan_body.h"
 
 namespace {
 
@@ -236,7 +237,7 @@ __device__ __forceinline__ void tile_out(const floatx4& acc, int n, int N, int q
 // one; the only exposed latencies are the first load and the input rows.  What bounds a block
 // is the bytes it keeps in flight, so all 16 waves are given weight rows to fetch.
 template <bool BF16>
-__global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_args a) {
+__device__ __forceinline__ void fused_mlp_block(const rec_fused_mlp_args& a, const int block) {
     typedef FM<BF16> C;
     typedef typename C::act_t act_t;
     constexpr int KCH = C::KCH;
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_arg
     __shared__ float red[FM_WAVES * 4 * 64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m0 = blockIdx.x * FM_ROWS;
+    const int m0 = block * FM_ROWS;
     const int li = lane & 15, q = lane >> 4;
     const LayerTab t(a);
 
@@ -388,14 +389,43 @@ __global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_arg
     }
 }
 
+template <bool BF16>
+__global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_args a) {
+    fused_mlp_block<BF16>(a, (int)blockIdx.x);
+}
+
+// The same stack with the bag-offsets scan in the first `scan_tiles` blocks of the launch: the
+// scan is a handful of latency-bound blocks that the pooling kernel waits for, and this stack is
+// what runs next to it on an otherwise idle device, so the two share one launch.  The scan
+// blocks come first because the last tile has the longest prefix to re-add.
+static_assert(FM_THREADS == SCAN_THREADS, "both roles use the same block size");
+template <bool BF16>
+__global__ __launch_bounds__(FM_THREADS) void fused_mlp_scan_kernel(rec_fused_mlp_args a, const int32_t* __restrict__ len,
+                                                                    int64_t n, int64_t* __restrict__ off, int vec_ok,
+                                                                    int scan_tiles) {
+    if ((int)blockIdx.x < scan_tiles) offsets_block(len, n, off, vec_ok, (int)blockIdx.x, true);
+    else fused_mlp_block<BF16>(a, (int)blockIdx.x - scan_tiles);
+}
+
 }  // namespace
 
-rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, hipStream_t s) {
+rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const rec_scan_job* scan, hipStream_t s) {
     const unsigned blocks = (unsigned)((a.B + FM_ROWS - 1) / FM_ROWS);
-    if (dt == REC_BF16)
+    if (scan) {
+        const int tiles = rec_scan_parallel_tiles(scan->n);
+        if (tiles < 1 || !scan->lengths || !scan->offsets) return REC_ERR_BAD_SHAPE;
+        const int vec_ok = (int)rec_aligned(scan->lengths, 16);
+        if (dt == REC_BF16)
+            hipLaunchKernelGGL(fused_mlp_scan_kernel<true>, dim3(blocks + tiles), dim3(FM_THREADS), 0, s, a, scan->lengths,
+                               scan->n, scan->offsets, vec_ok, tiles);
+        else
+            hipLaunchKernelGGL(fused_mlp_scan_kernel<false>, dim3(blocks + tiles), dim3(FM_THREADS), 0, s, a, scan->lengths,
+                               scan->n, scan->offsets, vec_ok, tiles);
+    } else if (dt == REC_BF16) {
         hipLaunchKernelGGL(fused_mlp_kernel<true>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
-    else
+    } else {
         hipLaunchKernelGGL(fused_mlp_kernel<false>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
+    }
     REC_CHECK_LAUNCH();
     return REC_OK;
 }

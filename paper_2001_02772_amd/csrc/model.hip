@@ -165,37 +165,49 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
     const ModelWorkspace w = carve(m, B, workspace);
     if (workspace_bytes < w.total) return REC_ERR_WORKSPACE;
     const int32_t V = m->T + 1, D = m->D;
+    const rec_scan_job scan = {lengths, (int64_t)m->T * B, rec_sls_workspace_offsets(w.sls)};
 
     if (m->concat) {
         // [ x | E_0 .. E_{T-1} ] is assembled in place: the pooling kernel and the dense stack (or
         // the copy of the dense features) write their columns of the joined rows directly
         const int32_t X = m->bottom_widths.back();
         const int64_t ldc = m->ld_inter;
-        rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X, ldc,
-                                        D, w.sls, w.sls_bytes, stream);
-        if (st != REC_OK) return st;
         if (m->bottom_W.empty()) {
+            rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X,
+                                            ldc, D, w.sls, w.sls_bytes, stream);
+            if (st != REC_OK) return st;
             const int64_t n4 = (int64_t)B * (X / 4);
             const unsigned blocks = (unsigned)std::min<int64_t>((n4 + 255) / 256, 4096);
             hipLaunchKernelGGL(copy_rows_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), dense, w.inter,
                                B, X, ldc);
             REC_CHECK_LAUNCH();
         } else {
-            st = rec_mlp_forward(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(),
-                                 (int32_t)m->bottom_W.size(), m->dt, REC_ACT_RELU, REC_ACT_RELU, dense, m->bottom_widths[0],
-                                 w.inter, ldc, B, w.mlp, w.mlp_bytes, stream);
+            // the offsets scan rides with the dense stack's first launch; the pooling follows both
+            rec_status st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B,
+                                                 w.inter + X, ldc, D, w.sls, w.sls_bytes, stream, REC_SLS_CHECK_ONLY);
+            if (st != REC_OK) return st;
+            st = rec_mlp_forward_scan(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(),
+                                      (int32_t)m->bottom_W.size(), m->dt, REC_ACT_RELU, REC_ACT_RELU, dense,
+                                      m->bottom_widths[0], w.inter, ldc, B, w.mlp, w.mlp_bytes, stream, &scan);
+            if (st != REC_OK) return st;
+            st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X, ldc,
+                                      D, w.sls, w.sls_bytes, stream, REC_SLS_POOL_ONLY);
             if (st != REC_OK) return st;
         }
         return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths.data(), (int32_t)m->top_W.size(), m->dt,
                                REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, ldc, prob, 1, B, w.mlp, w.mlp_bytes, stream);
     }
 
-    rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
-                                    (int64_t)V * D, D, w.sls, w.sls_bytes, stream);
+    // dense stack first: the offsets scan rides with its first launch, the pooling follows both
+    rec_status st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
+                                         (int64_t)V * D, D, w.sls, w.sls_bytes, stream, REC_SLS_CHECK_ONLY);
     if (st != REC_OK) return st;
-    st = rec_mlp_forward(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(), (int32_t)m->bottom_W.size(),
-                         m->dt, REC_ACT_RELU, REC_ACT_RELU, dense, m->bottom_widths[0], w.vecs, (int64_t)V * D, B, w.mlp,
-                         w.mlp_bytes, stream);
+    st = rec_mlp_forward_scan(m->bottom_W.data(), m->bottom_b.data(), m->bottom_widths.data(),
+                              (int32_t)m->bottom_W.size(), m->dt, REC_ACT_RELU, REC_ACT_RELU, dense, m->bottom_widths[0],
+                              w.vecs, (int64_t)V * D, B, w.mlp, w.mlp_bytes, stream, &scan);
+    if (st != REC_OK) return st;
+    st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
+                              (int64_t)V * D, D, w.sls, w.sls_bytes, stream, REC_SLS_POOL_ONLY);
     if (st != REC_OK) return st;
     st = rec_interact(w.vecs, B, V, D, w.inter, m->ld_inter, stream);
     if (st != REC_OK) return st;

@@ -56,7 +56,35 @@ struct rec_fused_mlp_args {
     int32_t B;
 };
 
-rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, hipStream_t s);
+// An offsets scan (lengths -> bag starts) that may ride along with another launch: the scan of
+// a batch is a few blocks of latency-bound work, so it shares a launch with the dense stack's
+// first fused run instead of standing alone in front of the pooling kernel.
+struct rec_scan_job {
+    const int32_t* lengths;
+    int64_t n;              // number of bags
+    int64_t* offsets;       // [n + 1]
+};
+int rec_scan_parallel_tiles(int64_t n);                          // > 0: independent tiles; 0: serial scan only
+rec_status rec_scan_launch(const rec_scan_job& job, hipStream_t s);
+
+// `scan` (may be NULL): also run this scan in the same launch; it must have parallel tiles.
+rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const rec_scan_job* scan, hipStream_t s);
+
+// rec_mlp_forward that also gets `scan` done no later than its first launch completes
+// (inside that launch when it is a fused run, by a launch of its own otherwise).
+rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, const int32_t* widths, int32_t n_layers,
+                                rec_dtype wdtype, rec_act hidden_act, rec_act final_act, const float* x, int64_t ldx,
+                                float* y, int64_t ldy, int32_t B, void* workspace, size_t workspace_bytes, void* stream,
+                                const rec_scan_job* scan);
+
+// rec_sls_forward in steps: all of it, only the argument checks, or only the pooling launch
+// (the caller has enqueued the scan into rec_sls_workspace_offsets() on the same stream).
+enum rec_sls_step { REC_SLS_ALL = 0, REC_SLS_CHECK_ONLY = 1, REC_SLS_POOL_ONLY = 2 };
+rec_status rec_sls_forward_step(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                                const int32_t* indices, int64_t n_indices, const int32_t* lengths, int32_t B, float* out,
+                                int64_t out_stride_b, int64_t out_stride_t, void* workspace, size_t workspace_bytes,
+                                void* stream, rec_sls_step step);
+int64_t* rec_sls_workspace_offsets(void* workspace);
 
 // ---- large bf16 layers (gemm_bf16.hip) --------------------------------------------------------
 int rec_gemm_bf16_split(int M, int N, int K);                    // 0: kernel does not apply

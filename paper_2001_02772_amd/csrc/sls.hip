@@ -8,124 +8,14 @@
 // VI-A name this the memory-bound, irregular part, so the kernel is organised
 // around keeping many independent 16-byte row loads in flight per wavefront.
 #include "rec_common.h"
+#include "scan_body.h"
 
 namespace {
 
 // ------------------------------------------------------------------ offsets scan
-constexpr int SCAN_THREADS = 1024;
-constexpr int SCAN_ITEMS = 4;
-constexpr int SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
-constexpr int SCAN_MAX_PARALLEL_TILES = 64;
-
-__device__ __forceinline__ int64_t wave_inclusive_scan(int64_t v, int lane) {
-#pragma unroll
-    for (int o = 1; o < REC_WAVE; o <<= 1) {
-        int64_t up = __shfl_up(v, o);
-        if (lane >= o) v += up;
-    }
-    return v;
-}
-
-// Block-wide exclusive scan of `v` (one value per thread) fused with a block-wide sum of
-// `extra`: returns the exclusive prefix of v, leaves the block totals in *v_total and
-// *extra_total.  smem holds two slots per wave.
-__device__ __forceinline__ int64_t block_scan_and_sum(int64_t v, int64_t extra, int64_t* smem, int64_t* v_total,
-                                                      int64_t* extra_total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n_waves = blockDim.x >> 6;
-    const int64_t incl = wave_inclusive_scan(v, lane);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) extra += __shfl_xor(extra, o);
-    __syncthreads();                       // smem may still be read from a previous call
-    if (lane == 63) {
-        smem[2 * wave] = incl;
-        smem[2 * wave + 1] = extra;
-    }
-    __syncthreads();
-    int64_t wave_base = 0, tot = 0, etot = 0;
-    for (int w = 0; w < n_waves; ++w) {
-        const int64_t s = smem[2 * w];
-        if (w < wave) wave_base += s;
-        tot += s;
-        etot += smem[2 * w + 1];
-    }
-    *v_total = tot;
-    *extra_total = etot;
-    return wave_base + incl - v;
-}
-
-// off[0] = 0, off[i+1] = off[i] + len[i].
-// A batch has a few tens of thousands of bags, so the scan is a latency chain, not a
-// bandwidth problem.  gridDim.x > 1: block k owns tile k (4096 lengths) and re-adds every
-// length before its tile with wide, independent loads (at most a few hundred KB, all in
-// L2) -- one launch, no inter-block waiting; the tile's own loads are issued first so both
-// latencies overlap, and one pass over LDS does the tile scan and the prefix sum together.
-// gridDim.x == 1 (very long inputs): a single block walks the tiles in order carrying the
-// running sum.
-__global__ __launch_bounds__(SCAN_THREADS) void offsets_kernel(const int32_t* __restrict__ len,
-                                                               int64_t n, int64_t* __restrict__ off,
-                                                               int vec_ok) {
-    __shared__ int64_t smem[2 * SCAN_THREADS / REC_WAVE];
-    const int tid = threadIdx.x;
-    const bool parallel = gridDim.x > 1;
-    int64_t carry = 0;
-    const int64_t tile_begin = parallel ? blockIdx.x : 0;
-    const int64_t tile_end = parallel ? tile_begin + 1 : (n + SCAN_TILE - 1) / SCAN_TILE;
-    for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
-        const int64_t first = tile * SCAN_TILE + (int64_t)tid * SCAN_ITEMS;
-        int32_t v[SCAN_ITEMS];
-        if (vec_ok && first + SCAN_ITEMS <= n) {
-            const int4 q = *reinterpret_cast<const int4*>(len + first);
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-        } else {
-#pragma unroll
-            for (int k = 0; k < SCAN_ITEMS; ++k) v[k] = (first + k < n) ? len[first + k] : 0;
-        }
-        int64_t part = 0;
-        if (parallel) {
-            const int64_t before = tile_begin * SCAN_TILE;          // a multiple of 4
-            if (vec_ok) {
-                const int4* __restrict__ len4 = reinterpret_cast<const int4*>(len);
-                const int64_t nv = before / 4;
-                for (int64_t i = tid; i < nv; i += 16 * SCAN_THREADS) {
-                    int4 q[16];
-#pragma unroll
-                    for (int k = 0; k < 16; ++k) {        // unconditional loads from clamped addresses
-                        const int64_t j = i + k * SCAN_THREADS;
-                        q[k] = len4[j < nv ? j : nv - 1];
-                    }
-#pragma unroll
-                    for (int k = 0; k < 16; ++k)
-                        if (i + k * SCAN_THREADS < nv) part += (int64_t)q[k].x + q[k].y + q[k].z + q[k].w;
-                }
-            } else {
-                for (int64_t i = tid; i < before; i += 8 * SCAN_THREADS) {
-                    int32_t q[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k)
-                        q[k] = (i + k * SCAN_THREADS < before) ? len[i + k * SCAN_THREADS] : 0;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) part += q[k];
-                }
-            }
-        }
-        int64_t s = 0;
-#pragma unroll
-        for (int k = 0; k < SCAN_ITEMS; ++k) s += v[k];
-        int64_t tot, before_tot;
-        int64_t run = block_scan_and_sum(s, part, smem, &tot, &before_tot) + carry + before_tot;
-        int64_t o[SCAN_ITEMS];
-#pragma unroll
-        for (int k = 0; k < SCAN_ITEMS; ++k) {
-            run += v[k];
-            o[k] = run;
-        }
-#pragma unroll
-        for (int k = 0; k < SCAN_ITEMS; ++k)
-            if (first + k < n) off[first + k + 1] = o[k];
-        carry += tot;
-    }
-    if (blockIdx.x == 0 && tid == 0) off[0] = 0;
+__global__ __launch_bounds__(SCAN_THREADS) void offsets_kernel(const int32_t* __restrict__ len, int64_t n,
+                                                               int64_t* __restrict__ off, int vec_ok) {
+    offsets_block(len, n, off, vec_ok, (int)blockIdx.x, gridDim.x > 1);
 }
 
 // ------------------------------------------------------------------ SLS
@@ -288,15 +178,25 @@ rec_status check_sparse_args(const int64_t* rows, int32_t T, const int32_t* indi
 }
 
 rec_status launch_offsets(const int32_t* lengths, int64_t n_bags, int64_t* offsets, hipStream_t s) {
-    const int64_t tiles = (n_bags + SCAN_TILE - 1) / SCAN_TILE;
-    const unsigned grid = (tiles >= 1 && tiles <= SCAN_MAX_PARALLEL_TILES) ? (unsigned)tiles : 1u;
-    hipLaunchKernelGGL(offsets_kernel, dim3(grid), dim3(SCAN_THREADS), 0, s, lengths, n_bags, offsets,
-                       (int)rec_aligned(lengths, 16));
+    const int tiles = rec_scan_parallel_tiles(n_bags);
+    hipLaunchKernelGGL(offsets_kernel, dim3(tiles > 0 ? (unsigned)tiles : 1u), dim3(SCAN_THREADS), 0, s, lengths,
+                       n_bags, offsets, (int)rec_aligned(lengths, 16));
     REC_CHECK_LAUNCH();
     return REC_OK;
 }
 
 }  // namespace
+
+int rec_scan_parallel_tiles(int64_t n) {
+    const int64_t tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    return (tiles >= 1 && tiles <= SCAN_MAX_PARALLEL_TILES) ? (int)tiles : 0;
+}
+
+rec_status rec_scan_launch(const rec_scan_job& job, hipStream_t s) {
+    return launch_offsets(job.lengths, job.n, job.offsets, s);
+}
+
+int64_t* rec_sls_workspace_offsets(void* workspace) { return static_cast<int64_t*>(workspace); }
 
 // XCD-aware block order on/off (read once; off by default until measured otherwise).
 static int sls_xcd_remap_default() {
@@ -347,6 +247,16 @@ rec_status rec_sls_forward(const float* const* tables, const int64_t* rows, int3
                            const int32_t* indices, int64_t n_indices, const int32_t* lengths, int32_t B,
                            float* out, int64_t out_stride_b, int64_t out_stride_t, void* workspace,
                            size_t workspace_bytes, void* stream) {
+    return rec_sls_forward_step(tables, rows, T, D, indices, n_indices, lengths, B, out, out_stride_b, out_stride_t,
+                                workspace, workspace_bytes, stream, REC_SLS_ALL);
+}
+
+}  // extern "C"
+
+rec_status rec_sls_forward_step(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                                const int32_t* indices, int64_t n_indices, const int32_t* lengths, int32_t B, float* out,
+                                int64_t out_stride_b, int64_t out_stride_t, void* workspace, size_t workspace_bytes,
+                                void* stream, rec_sls_step step) {
     rec_status st = check_sparse_args(rows, T, indices, n_indices, lengths, B);
     if (st != REC_OK) return st;
     if (!tables) return REC_ERR_NULL;
@@ -357,12 +267,17 @@ rec_status rec_sls_forward(const float* const* tables, const int64_t* rows, int3
         return REC_ERR_BAD_SHAPE;
     if (!workspace || !rec_aligned(workspace, 256) || workspace_bytes < rec_sls_workspace_bytes(T, B))
         return REC_ERR_WORKSPACE;
+    if (step == REC_SLS_CHECK_ONLY) return REC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     SlsWorkspace w = carve(workspace, T, B);
-    st = launch_offsets(lengths, (int64_t)T * B, w.offsets, s);
-    if (st != REC_OK) return st;
+    if (step == REC_SLS_ALL) {
+        st = launch_offsets(lengths, (int64_t)T * B, w.offsets, s);
+        if (st != REC_OK) return st;
+    }
     return rec_sls_launch(tables, T, D, indices, w.offsets, B, out, out_stride_b, out_stride_t, s);
 }
+
+extern "C" {
 
 rec_status rec_sls_forward_offsets(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
                                    const int32_t* indices, int64_t n_indices, const int64_t* offsets, int32_t B,
