@@ -238,6 +238,31 @@ typedef struct {
     int32_t B;
 } rec_request;
 
+/* A set of streams owned by the library for requests that may overlap on the device: default
+ * priority, not synchronised with the null stream (the caller orders them against whatever
+ * produced the inputs, e.g. by synchronising the device once after set-up).  1 <= n <= 16.
+ * Streams obtained from other run-times may share a hardware queue and then do not overlap;
+ * these are created back to back so that they are spread over the queues. */
+typedef struct rec_stream_pool rec_stream_pool;
+rec_status rec_stream_pool_create(int32_t n_streams, rec_stream_pool** out);
+void rec_stream_pool_destroy(rec_stream_pool* pool);                 /* waits for the streams' work first */
+int32_t rec_stream_pool_size(const rec_stream_pool* pool);
+void* rec_stream_pool_stream(const rec_stream_pool* pool, int32_t i); /* NULL if i is out of range */
+rec_status rec_stream_pool_synchronize(const rec_stream_pool* pool);
+
+/* Throughput mode (Section III-B counts completed work per second, not the latency of one
+ * request): request i runs on streams[i % n_streams] with workspaces[i % n_streams] and writes
+ * prob[i] (DEV fp32 [requests[i].B]).  Requests that share a stream run in order; requests on
+ * different streams overlap on the device, so the short latency-bound kernels of one request
+ * fill the gaps of another.  ASYNCHRONOUS on every stream; the caller orders the streams
+ * against whatever produced the inputs and synchronises them before reading prob.
+ * HOST: requests [n], prob [n] (array of DEV pointers), streams [n_streams], workspaces
+ * [n_streams] (DEV, each >= workspace_bytes >= rec_model_workspace_bytes(m, max B)).
+ * Stops at the first request that fails and returns its status. */
+rec_status rec_model_forward_many(const rec_model* m, const rec_request* requests, float* const* prob, int64_t n,
+                                  void* const* streams, void* const* workspaces, size_t workspace_bytes,
+                                  int32_t n_streams);
+
 /* Open-loop replay of a query trace on one device (SYNCHRONOUS, busy-waits on the host clock):
  * query q, made of requests[query_first[q] .. query_first[q+1]), is submitted to `stream` when
  * the host clock reaches arrival_s[q] (seconds from the start of the call, non-decreasing) and

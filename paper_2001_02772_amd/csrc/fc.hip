@@ -389,11 +389,31 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
     bool cur_bf16 = false;
     int32_t l = 0;
     int n_launch = 0;                 // alternates the two workspace halves
-    while (l < n_layers) {
-        // a run of narrow layers goes through the fused kernel, anything else through the tiled one
+    // a run of narrow layers goes through the fused kernel, anything else through the tiled one
+    auto narrow_run = [&](int32_t from) {
         int32_t run = 0;
-        while (l + run < n_layers && run < REC_FUSED_MAX_LAYERS && layer_is_narrow(widths[l + run], widths[l + run + 1], bf))
+        while (from + run < n_layers && run < REC_FUSED_MAX_LAYERS &&
+               layer_is_narrow(widths[from + run], widths[from + run + 1], bf))
             ++run;
+        return run;
+    };
+    if (scan) {
+        // the scan rides in the first fused launch of the stack; without one (or when it has no
+        // parallel tiles) it gets a launch of its own up front
+        bool can_ride = false;
+        for (int32_t i = 0; i < n_layers && !can_ride;) {
+            const int32_t run = narrow_run(i);
+            can_ride = run > 0;
+            i += run > 0 ? run : 1;
+        }
+        if (!can_ride || rec_scan_parallel_tiles(scan->n) < 1) {
+            const rec_status st = rec_scan_launch(*scan, s);
+            if (st != REC_OK) return st;
+            scan = nullptr;
+        }
+    }
+    while (l < n_layers) {
+        const int32_t run = narrow_run(l);
         const int32_t l_end = run > 0 ? l + run : l + 1;
         const bool last = (l_end == n_layers);
         void* dst = last ? static_cast<void*>(y)
@@ -417,19 +437,9 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
             a.y_bf16 = bf && !last;
             a.ldy = ldd;
             a.B = B;
-            if (scan && rec_scan_parallel_tiles(scan->n) < 1) {
-                st = rec_scan_launch(*scan, s);
-                if (st != REC_OK) return st;
-                scan = nullptr;
-            }
             st = rec_fused_mlp_launch(a, wdtype, scan, s);
             scan = nullptr;
         } else {
-            if (scan) {
-                st = rec_scan_launch(*scan, s);
-                if (st != REC_OK) return st;
-                scan = nullptr;
-            }
             st = launch_layer(cur, cur_bf16, ld, W[l], wdtype, bias[l], B, widths[l], widths[l + 1],
                               last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, partial, s);
         }

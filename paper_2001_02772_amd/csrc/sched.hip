@@ -9,6 +9,7 @@
 #include <chrono>
 #include <cmath>
 #include <limits>
+#include <new>
 #include <vector>
 
 #include "rec_common.h"
@@ -50,7 +51,52 @@ struct RateTest {
 
 }  // namespace
 
+struct rec_stream_pool {
+    std::vector<hipStream_t> streams;
+};
+
 extern "C" {
+
+rec_status rec_stream_pool_create(int32_t n_streams, rec_stream_pool** out) {
+    if (!out) return REC_ERR_NULL;
+    *out = nullptr;
+    if (n_streams < 1 || n_streams > 16) return REC_ERR_BAD_SHAPE;
+    rec_stream_pool* p = new (std::nothrow) rec_stream_pool;
+    if (!p) return REC_ERR_DEVICE;
+    for (int32_t i = 0; i < n_streams; ++i) {
+        hipStream_t s = nullptr;
+        if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) {
+            rec_stream_pool_destroy(p);
+            return REC_ERR_DEVICE;
+        }
+        p->streams.push_back(s);
+    }
+    *out = p;
+    return REC_OK;
+}
+
+void rec_stream_pool_destroy(rec_stream_pool* pool) {
+    if (!pool) return;
+    for (hipStream_t s : pool->streams) {
+        (void)hipStreamSynchronize(s);
+        (void)hipStreamDestroy(s);
+    }
+    delete pool;
+}
+
+int32_t rec_stream_pool_size(const rec_stream_pool* pool) { return pool ? (int32_t)pool->streams.size() : 0; }
+
+void* rec_stream_pool_stream(const rec_stream_pool* pool, int32_t i) {
+    if (!pool || i < 0 || i >= (int32_t)pool->streams.size()) return nullptr;
+    return pool->streams[(size_t)i];
+}
+
+rec_status rec_stream_pool_synchronize(const rec_stream_pool* pool) {
+    if (!pool) return REC_ERR_NULL;
+    for (hipStream_t s : pool->streams)
+        if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
+    return REC_OK;
+}
 
 double rec_sched_query_service(int64_t n, int64_t batch, const double* table) {
     if (n < 0 || batch < 1 || !table) return kNaN;
@@ -117,6 +163,22 @@ int64_t rec_sched_hill_climb(const double* qps, int64_t n_candidates) {
         keep = next;
     }
     return keep;
+}
+
+rec_status rec_model_forward_many(const rec_model* m, const rec_request* requests, float* const* prob, int64_t n,
+                                  void* const* streams, void* const* workspaces, size_t workspace_bytes,
+                                  int32_t n_streams) {
+    if (n < 0 || n_streams < 1) return REC_ERR_BAD_SHAPE;
+    if (n == 0) return REC_OK;
+    if (!m || !requests || !prob || !streams || !workspaces) return REC_ERR_NULL;
+    for (int64_t i = 0; i < n; ++i) {
+        const rec_request& rq = requests[i];
+        const int32_t k = (int32_t)(i % n_streams);
+        const rec_status st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[i],
+                                                workspaces[k], workspace_bytes, streams[k]);
+        if (st != REC_OK) return st;
+    }
+    return REC_OK;
 }
 
 rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, const int64_t* query_first,

@@ -32,7 +32,9 @@ EXPORTS = (
     "rec_interact",
     "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
     "rec_sched_query_service", "rec_sched_fifo_latencies", "rec_sched_percentile", "rec_sched_max_qps",
-    "rec_sched_hill_climb", "rec_serve_trace",
+    "rec_sched_hill_climb", "rec_serve_trace", "rec_model_forward_many",
+    "rec_stream_pool_create", "rec_stream_pool_destroy", "rec_stream_pool_size", "rec_stream_pool_stream",
+    "rec_stream_pool_synchronize",
 )
 
 
@@ -108,6 +110,18 @@ def lib():
     L.rec_sched_max_qps.argtypes = [vp, vp, i64, C.c_double, C.c_double, i32]
     L.rec_sched_hill_climb.restype = i64
     L.rec_sched_hill_climb.argtypes = [vp, i64]
+    L.rec_stream_pool_create.restype = C.c_int
+    L.rec_stream_pool_create.argtypes = [i32, vp]
+    L.rec_stream_pool_destroy.restype = None
+    L.rec_stream_pool_destroy.argtypes = [vp]
+    L.rec_stream_pool_size.restype = i32
+    L.rec_stream_pool_size.argtypes = [vp]
+    L.rec_stream_pool_stream.restype = vp
+    L.rec_stream_pool_stream.argtypes = [vp, i32]
+    L.rec_stream_pool_synchronize.restype = C.c_int
+    L.rec_stream_pool_synchronize.argtypes = [vp]
+    L.rec_model_forward_many.restype = C.c_int
+    L.rec_model_forward_many.argtypes = [vp, vp, vp, i64, vp, vp, sz, i32]
     L.rec_serve_trace.restype = C.c_int
     L.rec_serve_trace.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
     _lib = L
@@ -358,6 +372,55 @@ def sched_hill_climb(qps) -> int:
 class _Request(C.Structure):
     _fields_ = [("dense", C.c_void_p), ("indices", C.c_void_p), ("n_indices", C.c_int64), ("lengths", C.c_void_p),
                 ("B", C.c_int32)]
+
+
+class _PoolStream:
+    def __init__(self, handle: int):
+        self.cuda_stream = handle
+
+
+class StreamPool:
+    """Streams owned by the library (rec_stream_pool_*); .streams[i].cuda_stream is the raw handle."""
+
+    def __init__(self, n: int):
+        h = C.c_void_p(0)
+        _check(lib().rec_stream_pool_create(n, C.addressof(h)), "rec_stream_pool_create")
+        self._h = h
+        self.streams = [_PoolStream(lib().rec_stream_pool_stream(h, i)) for i in range(lib().rec_stream_pool_size(h))]
+
+    def synchronize(self):
+        _check(lib().rec_stream_pool_synchronize(self._h), "rec_stream_pool_synchronize")
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().rec_stream_pool_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+class ForwardMany:
+    """Marshalled arguments of rec_model_forward_many for a fixed list of requests (device
+    batches), outputs, streams and workspaces; launch() enqueues them all and returns at once."""
+
+    def __init__(self, model: "Model", requests, probs, streams, workspaces=None):
+        self.model, self.n, self.keep = model, len(requests), (requests, probs, streams)
+        self.reqs = (_Request * max(self.n, 1))()
+        for i, r in enumerate(requests):
+            self.reqs[i] = _Request(_ptr(r.dense), _ptr(r.indices), r.indices.numel(), _ptr(r.lengths), r.B)
+        self.probs = (C.c_void_p * max(self.n, 1))(*[_ptr(p) for p in probs])
+        max_b = max([r.B for r in requests] + [1])
+        need = model.workspace_bytes(max_b)
+        self.ws = workspaces if workspaces is not None else [_workspace(need, model.device) for _ in streams]
+        self.ws_bytes = min(w.numel() for w in self.ws)
+        self.streams = (C.c_void_p * len(streams))(*[s.cuda_stream for s in streams])
+        self.wsp = (C.c_void_p * len(streams))(*[_ptr(w) for w in self.ws])
+
+    def launch(self):
+        st = lib().rec_model_forward_many(self.model._h, C.addressof(self.reqs), C.addressof(self.probs), self.n,
+                                          C.addressof(self.streams), C.addressof(self.wsp), self.ws_bytes,
+                                          len(self.streams))
+        _check(st, "rec_model_forward_many")
 
 
 def serve_trace(model: "Model", queries, arrival_s):

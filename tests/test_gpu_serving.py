@@ -82,3 +82,39 @@ def test_replay_rejects_bad_traces(setup):
     with pytest.raises(rec.RecError):
         rec.serve_trace(model, queries, np.array([-1.0, 0.0]))
     assert rec.serve_trace(model, [], np.zeros(0)).size == 0
+
+
+def test_forward_many_matches_single_forward(setup):
+    rec, workload, cfg, model, batch = setup
+    sizes = [5, 1, 16, 4, 7, 3, 9, 12, 2]
+    reqs, start = [], 0
+    for n in sizes:
+        reqs.append(workload.DeviceBatch(workload.slice_batch(batch, cfg.T, start, n)))
+        start += n
+    want = [model.forward(r.dense, r.indices, r.lengths, r.B).clone() for r in reqs]
+    torch.cuda.synchronize()
+    for n_streams in (1, 3):
+        pool = rec.StreamPool(n_streams)
+        streams = pool.streams
+        assert len(streams) == n_streams and all(s.cuda_stream for s in streams)
+        probs = [torch.zeros(r.B, dtype=torch.float32, device="cuda") for r in reqs]
+        torch.cuda.synchronize()
+        fm = rec.ForwardMany(model, reqs, probs, streams)
+        fm.launch()
+        pool.synchronize()
+        for p, w in zip(probs, want):
+            assert torch.equal(p, w)
+    # against the oracle as well
+    sub = cfg.replace(B=sum(sizes))
+    hb = workload.slice_batch(batch, cfg.T, 0, sum(sizes))
+    small, idx = compact_tables(sub, hb)
+    assert_close(torch.cat(probs).cpu().numpy(), oracle_forward(sub, small, hb, indices=idx), TOL_F32, "forward_many")
+    with pytest.raises(rec.RecError):
+        bad = rec.ForwardMany(model, reqs, probs, streams)
+        bad.ws_bytes = 16                                            # workspace too small
+        bad.launch()
+    torch.cuda.synchronize()
+    with pytest.raises(rec.RecError):
+        rec.StreamPool(0)
+    with pytest.raises(rec.RecError):
+        rec.StreamPool(17)
