@@ -241,8 +241,10 @@ typedef struct {
 /* A set of streams owned by the library for requests that may overlap on the device: default
  * priority, not synchronised with the null stream (the caller orders them against whatever
  * produced the inputs, e.g. by synchronising the device once after set-up).  1 <= n <= 16.
- * Streams obtained from other run-times may share a hardware queue and then do not overlap;
- * these are created back to back so that they are spread over the queues. */
+ * Streams that share one of the runtime's few hardware queues do not overlap, and which
+ * streams share is settled when they are created: create the pool before the process creates
+ * other streams or runs other device work (measured: a pool created first spreads over 4 queues,
+ * one created after a framework's set-up behaved like 2 streams). */
 typedef struct rec_stream_pool rec_stream_pool;
 rec_status rec_stream_pool_create(int32_t n_streams, rec_stream_pool** out);
 void rec_stream_pool_destroy(rec_stream_pool* pool);                 /* waits for the streams' work first */
