@@ -223,7 +223,9 @@ def main():
         per_b[str(Bs)] = {"samples_per_s": Bs / s, "us_per_batch": s * 1e6,
                           "single_stream": {"samples_per_s": Bs / s1, "us_per_batch": s1 * 1e6}}
 
-    out = {"metric": "samples/sec per batch size + SLS achieved HBM GB/s (RMC2-shaped, 1 GPU)",
+    metric = ("samples/sec per batch size + SLS achieved HBM GB/s (RMC2-shaped, 1 GPU)" if cfg.name == "rmc2"
+              else f"samples/sec per batch size ({cfg.name}-shaped, 1 GPU)")
+    out = {"metric": metric,
            "value": value, "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
            "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if cfg.bf16 else "f32", "data": "synthetic",
@@ -262,7 +264,8 @@ def main():
         out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
 
     if a.sched:
-        out["batch_size_tuning"] = batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np)
+        out["batch_size_tuning"] = batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
+                                                     pool_streams=streams if a.streams > 1 else None)
 
     if not a.no_cpu_baseline:
         base, p_cpu = cpu_baseline(cfg, host_batches[0])
@@ -315,7 +318,7 @@ TABLE_II_TARGET_MS = {"rmc1": 100.0, "rmc2": 400.0, "rmc2-uniform": 400.0, "rmc3
 
 
 def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
-                      sla_ms=(0.25, 0.5, 1.0, 5.0), live_load=0.8):
+                      sla_ms=(0.25, 0.5, 1.0, 5.0), live_load=0.8, pool_streams=None):
     """Batch-size hill climb on latency-bounded throughput (Sections III-B, IV-C), then an open-loop
     check of the prediction with Poisson arrivals on the device (Section III-C).
 
@@ -373,15 +376,94 @@ def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
         src = [gen.batch(100 + k, B=1000) for k in range(4)]
         staged = [[workload.DeviceBatch(workload.slice_batch(src[q % len(src)], cfg.T, s, c))
                    for s, c in rec.split_query(int(n), Bs)] for q, n in enumerate(sizes.tolist())]
-        rec.serve_trace(model, staged[:100], np.zeros(100))                      # warm
-        live = rec.serve_trace(model, staged, unit / rate)
+        one = rec.ServeTrace(model, staged)
+        one.run(np.zeros(len(staged)))                                           # warm
+        live = one.run(unit / rate)
         want = rec.sched_fifo_latencies(unit / rate, svc[Bs])
         res["live"] = {"target_ms": sla, "batch": Bs, "offered_qps": rate, "load_vs_predicted_max": live_load,
                        "p95_ms": rec.sched_percentile(live, 0.95) * 1e3, "p50_ms": rec.sched_percentile(live, 0.5) * 1e3,
                        "predicted_p95_ms": rec.sched_percentile(want, 0.95) * 1e3,
                        "within_target": bool(rec.sched_percentile(live, 0.95) <= sla * 1e-3),
                        "items_per_s": float(sizes.sum() * rate / len(sizes))}
+        # latency-bounded throughput measured, not modelled: the largest offered rate whose live
+        # p95 stays under the target, one stream and the stream pool
+        res["live_max_qps"] = {"target_ms": sla, "batch": Bs, "predicted_single_stream": pick["chosen_max_qps"],
+                               "single_stream": live_max_qps(one, unit, sla * 1e-3, pick["chosen_max_qps"], rec)}
+        if pool_streams is not None:
+            many = rec.ServeTrace(model, staged, pool_streams)
+            many.run(np.zeros(len(staged)))
+            res["live_max_qps"][f"{len(pool_streams)}_streams"] = live_max_qps(many, unit, sla * 1e-3,
+                                                                                pick["chosen_max_qps"], rec)
+        del one, staged
+        if pool_streams is not None:
+            del many
+    # the hill climb run the way the paper runs it: on measured rates, here with the stream pool
+    if pool_streams is not None:
+        res["live_hill_climb"] = {f"{t}ms": live_hill_climb(cfg, model, gen, sizes, unit, t * 1e-3, cands, pool_streams,
+                                                            rec, workload, np) for t in (1.0, 5.0)}
     return res
+
+
+def live_hill_climb(cfg, model, gen, sizes, unit, sla_s, cands, pool_streams, rec, workload, np, n=400):
+    """Section IV-C on live measurements: for batch sizes 1, 2, 4, ... measure the largest Poisson
+    rate the device sustains with p95 <= target (first `n` queries of the trace, requests spread
+    over the stream pool) and climb until that rate degrades."""
+    src = [gen.batch(100 + k, B=1000) for k in range(4)]
+    qps = []
+    for Bs in cands:
+        staged = [[workload.DeviceBatch(workload.slice_batch(src[q % len(src)], cfg.T, s, c))
+                   for s, c in rec.split_query(int(m), Bs)] for q, m in enumerate(sizes[:n].tolist())]
+        tr = rec.ServeTrace(model, staged, pool_streams)
+        tr.run(np.zeros(n))                                               # warm
+        idle = tr.run(np.arange(n) * 2.0 * sla_s)                         # no queueing: service times alone
+        if rec.sched_percentile(idle, 0.95) > sla_s:
+            qps.append(0.0)
+        else:
+            start = max(qps[-1] if qps else 0.0, 0.5 / sla_s)
+            qps.append(live_max_qps(tr, unit[:n], sla_s, start, rec, bracket_steps=14, bisect_steps=4))
+        del tr, staged
+        print(f"[sched] live climb, target {sla_s * 1e3:g} ms, batch {Bs}: {qps[-1]:.0f} queries/s", file=sys.stderr, flush=True)
+        if len(qps) > 1 and qps[-1] < qps[-2]:
+            break                                                          # degraded: the climb stops here
+    k = rec.sched_hill_climb(qps)
+    return {"queries": n, "max_qps": {str(B): q for B, q in zip(cands, qps)}, "chosen_batch": cands[k],
+            "chosen_max_qps": qps[k]}
+
+
+def live_max_qps(trace, unit, sla_s, start, rec, grow=1.25, bracket_steps=10, bisect_steps=6):
+    """Largest offered rate (queries/s) for which a live replay keeps p95 <= sla_s: bracket from
+    `start` by factors of `grow`, then bisect.  Each probe replays the whole trace once."""
+    ok = lambda r: rec.sched_percentile(trace.run(unit / r), 0.95) <= sla_s
+    lo = hi = None
+    r = start
+    if ok(r):
+        lo = r
+        for _ in range(bracket_steps):
+            r *= grow
+            if ok(r):
+                lo = r
+            else:
+                hi = r
+                break
+    else:
+        hi = r
+        for _ in range(bracket_steps):
+            r /= grow
+            if ok(r):
+                lo = r
+                break
+            hi = r
+    if lo is None:
+        return 0.0
+    if hi is None:
+        return lo
+    for _ in range(bisect_steps):
+        mid = 0.5 * (lo + hi)
+        if ok(mid):
+            lo = mid
+        else:
+            hi = mid
+    return lo
 
 
 if __name__ == "__main__":

@@ -184,47 +184,76 @@ rec_status rec_model_forward_many(const rec_model* m, const rec_request* request
 rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, const int64_t* query_first,
                            const double* arrival_s, int64_t n_queries, float* prob, void* workspace,
                            size_t workspace_bytes, void* stream, double* latency_s) {
-    if (n_queries < 0) return REC_ERR_BAD_SHAPE;
+    return rec_serve_trace_many(m, requests, query_first, arrival_s, n_queries, &prob, &workspace, workspace_bytes, &stream,
+                                1, latency_s);
+}
+
+rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests, const int64_t* query_first,
+                                const double* arrival_s, int64_t n_queries, float* const* prob,
+                                void* const* workspaces, size_t workspace_bytes, void* const* streams,
+                                int32_t n_streams, double* latency_s) {
+    if (n_queries < 0 || n_streams < 1) return REC_ERR_BAD_SHAPE;
     if (n_queries == 0) return REC_OK;
-    if (!m || !requests || !query_first || !arrival_s || !latency_s || !prob) return REC_ERR_NULL;
+    if (!m || !requests || !query_first || !arrival_s || !latency_s || !prob || !workspaces || !streams) return REC_ERR_NULL;
+    for (int32_t k = 0; k < n_streams; ++k)
+        if (!prob[k]) return REC_ERR_NULL;
     for (int64_t q = 0; q < n_queries; ++q) {
         if (query_first[q + 1] < query_first[q] || arrival_s[q] < 0.0) return REC_ERR_BAD_SHAPE;
         if (q > 0 && arrival_s[q] < arrival_s[q - 1]) return REC_ERR_BAD_SHAPE;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    std::vector<hipEvent_t> done((size_t)n_queries + 1, nullptr);
+    // done[q] marks the completion of query q; origin[k] is time zero as stream k sees it
+    std::vector<hipEvent_t> done((size_t)n_queries, nullptr), origin((size_t)n_streams, nullptr);
     auto cleanup = [&]() {
         for (hipEvent_t e : done)
             if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : origin)
+            if (e) (void)hipEventDestroy(e);
+    };
+    auto sync_all = [&]() {
+        bool ok = true;
+        for (int32_t k = 0; k < n_streams; ++k) ok = (hipStreamSynchronize(static_cast<hipStream_t>(streams[k])) == hipSuccess) && ok;
+        return ok;
     };
     for (auto& e : done)
         if (hipEventCreate(&e) != hipSuccess) {
             cleanup();
             return REC_ERR_DEVICE;
         }
-    // time zero: the stream is idle and done[0] has just completed, so device timestamps measured
-    // from done[0] and host time measured from t0 share an origin to within the sync latency
-    if (hipEventRecord(done[0], s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) {
+    for (auto& e : origin)
+        if (hipEventCreate(&e) != hipSuccess) {
+            cleanup();
+            return REC_ERR_DEVICE;
+        }
+    // time zero: every stream is idle and its origin event has just completed, so device
+    // timestamps measured from it and host time measured from t0 share an origin to within the
+    // latency of the synchronisation
+    bool ok = sync_all();
+    for (int32_t k = 0; k < n_streams && ok; ++k)
+        ok = hipEventRecord(origin[(size_t)k], static_cast<hipStream_t>(streams[k])) == hipSuccess;
+    ok = ok && sync_all();
+    if (!ok) {
         cleanup();
         return REC_ERR_DEVICE;
     }
     const auto t0 = std::chrono::steady_clock::now();
     rec_status st = REC_OK;
     for (int64_t q = 0; q < n_queries && st == REC_OK; ++q) {
+        const int32_t k = (int32_t)(q % n_streams);
         while (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < arrival_s[q]) {
         }
         for (int64_t r = query_first[q]; r < query_first[q + 1] && st == REC_OK; ++r) {
             const rec_request& rq = requests[r];
-            st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob, workspace,
-                                   workspace_bytes, stream);
+            st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[k], workspaces[k],
+                                   workspace_bytes, streams[k]);
         }
-        if (st == REC_OK && hipEventRecord(done[(size_t)q + 1], s) != hipSuccess) st = REC_ERR_DEVICE;
+        if (st == REC_OK && hipEventRecord(done[(size_t)q], static_cast<hipStream_t>(streams[k])) != hipSuccess)
+            st = REC_ERR_DEVICE;
     }
-    if (hipStreamSynchronize(s) != hipSuccess && st == REC_OK) st = REC_ERR_DEVICE;
+    if (!sync_all() && st == REC_OK) st = REC_ERR_DEVICE;
     if (st == REC_OK) {
         for (int64_t q = 0; q < n_queries; ++q) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, done[0], done[(size_t)q + 1]) != hipSuccess) {
+            if (hipEventElapsedTime(&ms, origin[(size_t)(q % n_streams)], done[(size_t)q]) != hipSuccess) {
                 st = REC_ERR_DEVICE;
                 break;
             }

@@ -32,7 +32,7 @@ EXPORTS = (
     "rec_interact",
     "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
     "rec_sched_query_service", "rec_sched_fifo_latencies", "rec_sched_percentile", "rec_sched_max_qps",
-    "rec_sched_hill_climb", "rec_serve_trace", "rec_model_forward_many",
+    "rec_sched_hill_climb", "rec_serve_trace", "rec_serve_trace_many", "rec_model_forward_many",
     "rec_stream_pool_create", "rec_stream_pool_destroy", "rec_stream_pool_size", "rec_stream_pool_stream",
     "rec_stream_pool_synchronize",
 )
@@ -122,6 +122,8 @@ def lib():
     L.rec_stream_pool_synchronize.argtypes = [vp]
     L.rec_model_forward_many.restype = C.c_int
     L.rec_model_forward_many.argtypes = [vp, vp, vp, i64, vp, vp, sz, i32]
+    L.rec_serve_trace_many.restype = C.c_int
+    L.rec_serve_trace_many.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, i32, vp]
     L.rec_serve_trace.restype = C.c_int
     L.rec_serve_trace.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
     _lib = L
@@ -423,20 +425,39 @@ class ForwardMany:
         _check(st, "rec_model_forward_many")
 
 
-def serve_trace(model: "Model", queries, arrival_s):
-    """queries: list (one per query) of lists of request objects with .dense .indices .lengths .B
-    (device tensors).  Returns per-query latencies in seconds (NumPy float64)."""
-    flat = [r for q in queries for r in q]
-    reqs = (_Request * max(len(flat), 1))()
-    for i, r in enumerate(flat):
-        reqs[i] = _Request(_ptr(r.dense), _ptr(r.indices), r.indices.numel(), _ptr(r.lengths), r.B)
-    first = _host_i64(np.concatenate([[0], np.cumsum([len(q) for q in queries])]))
-    arrival_s = _host_f64(arrival_s)
-    max_b = max([r.B for r in flat] + [1])
-    prob = torch.empty(max_b, dtype=torch.float32, device=model.device)
-    ws = model.workspace(max_b)
-    lat = np.empty(len(queries), dtype=np.float64)
-    st = lib().rec_serve_trace(model._h, C.addressof(reqs), first.ctypes.data, arrival_s.ctypes.data, len(queries),
-                               _ptr(prob), _ptr(ws), ws.numel(), _stream(), lat.ctypes.data)
-    _check(st, "rec_serve_trace")
-    return lat
+class ServeTrace:
+    """Marshalled arguments of rec_serve_trace_many for a fixed list of queries (each a list of
+    device batches); run(arrival_s) replays the trace and returns per-query latencies in seconds.
+    streams: objects with .cuda_stream (None: torch's current stream)."""
+
+    def __init__(self, model: "Model", queries, streams=None):
+        self.model, self.keep = model, queries
+        flat = [r for q in queries for r in q]
+        self.n = len(queries)
+        self.reqs = (_Request * max(len(flat), 1))()
+        for i, r in enumerate(flat):
+            self.reqs[i] = _Request(_ptr(r.dense), _ptr(r.indices), r.indices.numel(), _ptr(r.lengths), r.B)
+        self.first = _host_i64(np.concatenate([[0], np.cumsum([len(q) for q in queries])]))
+        handles = [_stream()] if streams is None else [s.cuda_stream for s in streams]
+        max_b = max([r.B for r in flat] + [1])
+        self.ws_bytes = model.workspace_bytes(max_b)
+        self.ws = [_workspace(self.ws_bytes, model.device) for _ in handles]
+        self.prob = [torch.empty(max_b, dtype=torch.float32, device=model.device) for _ in handles]
+        self.streams = (C.c_void_p * len(handles))(*handles)
+        self.wsp = (C.c_void_p * len(handles))(*[_ptr(w) for w in self.ws])
+        self.probp = (C.c_void_p * len(handles))(*[_ptr(p) for p in self.prob])
+
+    def run(self, arrival_s):
+        arrival_s = _host_f64(arrival_s)
+        assert arrival_s.size == self.n
+        lat = np.empty(self.n, dtype=np.float64)
+        st = lib().rec_serve_trace_many(self.model._h, C.addressof(self.reqs), self.first.ctypes.data,
+                                        arrival_s.ctypes.data, self.n, C.addressof(self.probp), C.addressof(self.wsp),
+                                        self.ws_bytes, C.addressof(self.streams), len(self.streams), lat.ctypes.data)
+        _check(st, "rec_serve_trace_many")
+        return lat
+
+
+def serve_trace(model: "Model", queries, arrival_s, streams=None):
+    """One replay; see ServeTrace."""
+    return ServeTrace(model, queries, streams).run(arrival_s)
