@@ -118,3 +118,26 @@ def test_forward_many_matches_single_forward(setup):
         rec.StreamPool(0)
     with pytest.raises(rec.RecError):
         rec.StreamPool(17)
+
+
+def test_replay_over_stream_pool(setup):
+    rec, workload, cfg, model, batch = setup
+    sizes = [5, 1, 9, 4, 7, 3, 6, 2]
+    queries = split(rec, workload, cfg, batch, sizes, 4)
+    pool = rec.StreamPool(3)
+    tr = rec.ServeTrace(model, queries, pool.streams)
+    print("[serving] pool burst replay", flush=True)
+    lat = tr.run(np.zeros(len(sizes)))
+    assert np.all(lat > 0) and lat.max() < 1.0
+    for k in range(3):                       # queries that share a stream complete in order
+        assert np.all(np.diff(lat[k::3]) > 0)
+    print("[serving] pool spaced replay", flush=True)
+    gap = 5e-3
+    lat2 = tr.run(np.arange(len(sizes)) * gap)
+    assert np.all(lat2 > 0) and np.all(lat2 < gap)
+    # each stream's output buffer holds the last request of the last query that ran on it
+    for k in range(3):
+        q = max(i for i in range(len(sizes)) if i % 3 == k)
+        last = queries[q][-1]
+        want = model.forward(last.dense, last.indices, last.lengths, last.B)
+        assert torch.equal(tr.prob[k][: last.B], want)
