@@ -53,3 +53,23 @@ def test_size_queries(rec):
     assert rec.sls_workspace_bytes(0, 4) == 0
     assert rec.mlp_workspace_bytes([884, 512, 128, 1], 1024, rec.F32) >= 2 * 1024 * 512 * 4
     assert rec.mlp_workspace_bytes([13, 1], 10, rec.F32) == 0
+
+
+def test_serving_entry_points_reject_bad_arguments_on_the_host(rec):
+    """Argument checks that return before any device call, so they run without a GPU."""
+    import ctypes as C
+    L = rec.lib()
+    h = C.c_void_p(0)
+    for n in (0, -1, 17):
+        assert L.rec_stream_pool_create(n, C.addressof(h)) == rec.ERR_BAD_SHAPE and not h.value
+    assert L.rec_stream_pool_create(4, None) == rec.ERR_NULL
+    assert L.rec_stream_pool_size(None) == 0 and L.rec_stream_pool_stream(None, 0) is None
+    assert L.rec_stream_pool_synchronize(None) == rec.ERR_NULL
+    L.rec_stream_pool_destroy(None)
+    assert L.rec_model_forward_many(None, None, None, 0, None, None, 0, 1) == rec.OK         # nothing to do
+    assert L.rec_model_forward_many(None, None, None, 3, None, None, 0, 0) == rec.ERR_BAD_SHAPE
+    assert L.rec_model_forward_many(None, None, None, 3, None, None, 0, 2) == rec.ERR_NULL
+    assert L.rec_serve_trace_many(None, None, None, None, 0, None, None, 0, None, 1, None) == rec.OK
+    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 0, None) == rec.ERR_BAD_SHAPE
+    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 1, None) == rec.ERR_NULL
+    assert L.rec_serve_trace(None, None, None, None, -1, None, None, 0, None, None) == rec.ERR_BAD_SHAPE
