@@ -260,7 +260,8 @@ rec_status rec_stream_pool_synchronize(const rec_stream_pool* pool);
  * against whatever produced the inputs and synchronises them before reading prob.
  * HOST: requests [n], prob [n] (array of DEV pointers), streams [n_streams], workspaces
  * [n_streams] (DEV, each >= workspace_bytes >= rec_model_workspace_bytes(m, max B)).
- * Stops at the first request that fails and returns its status. */
+ * A long list (n >= 8 n_streams) is enqueued by one host thread per stream.  A request that
+ * fails ends its stream's list; the status of the lowest-numbered failing request is returned. */
 rec_status rec_model_forward_many(const rec_model* m, const rec_request* requests, float* const* prob, int64_t n,
                                   void* const* streams, void* const* workspaces, size_t workspace_bytes,
                                   int32_t n_streams);

@@ -10,6 +10,7 @@
 #include <cmath>
 #include <limits>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "rec_common.h"
@@ -171,14 +172,53 @@ rec_status rec_model_forward_many(const rec_model* m, const rec_request* request
     if (n < 0 || n_streams < 1) return REC_ERR_BAD_SHAPE;
     if (n == 0) return REC_OK;
     if (!m || !requests || !prob || !streams || !workspaces) return REC_ERR_NULL;
-    for (int64_t i = 0; i < n; ++i) {
-        const rec_request& rq = requests[i];
-        const int32_t k = (int32_t)(i % n_streams);
-        const rec_status st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[i],
-                                                workspaces[k], workspace_bytes, streams[k]);
-        if (st != REC_OK) return st;
+    // requests of stream k: k, k + S, k + 2S, ... in order; returns the first failure on that stream
+    auto run_stream = [&](int32_t k, int64_t* failed_at) {
+        for (int64_t i = k; i < n; i += n_streams) {
+            const rec_request& rq = requests[i];
+            const rec_status st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[i],
+                                                    workspaces[k], workspace_bytes, streams[k]);
+            if (st != REC_OK) {
+                *failed_at = i;
+                return st;
+            }
+        }
+        *failed_at = n;
+        return REC_OK;
+    };
+    // A forward is five to seven launches of a few microseconds of host time each; with short
+    // batches the device outruns one enqueuing thread, so a long list gets a thread per stream.
+    if (n_streams == 1 || n < 8 * (int64_t)n_streams) {
+        for (int64_t i = 0; i < n; ++i) {
+            const rec_request& rq = requests[i];
+            const int32_t k = (int32_t)(i % n_streams);
+            const rec_status st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[i],
+                                                    workspaces[k], workspace_bytes, streams[k]);
+            if (st != REC_OK) return st;
+        }
+        return REC_OK;
     }
-    return REC_OK;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return REC_ERR_DEVICE;
+    std::vector<rec_status> status((size_t)n_streams, REC_OK);
+    std::vector<int64_t> failed_at((size_t)n_streams, n);
+    std::vector<std::thread> workers;
+    for (int32_t k = 1; k < n_streams; ++k)
+        workers.emplace_back([&, k]() {
+            if (hipSetDevice(device) != hipSuccess) {
+                status[(size_t)k] = REC_ERR_DEVICE;
+                failed_at[(size_t)k] = k;
+                return;
+            }
+            status[(size_t)k] = run_stream(k, &failed_at[(size_t)k]);
+        });
+    status[0] = run_stream(0, &failed_at[0]);
+    for (std::thread& t : workers) t.join();
+    // report the failure of the lowest-numbered request
+    int32_t worst = 0;
+    for (int32_t k = 1; k < n_streams; ++k)
+        if (failed_at[(size_t)k] < failed_at[(size_t)worst]) worst = k;
+    return status[(size_t)worst];
 }
 
 rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, const int64_t* query_first,

@@ -104,6 +104,17 @@ def test_forward_many_matches_single_forward(setup):
         pool.synchronize()
         for p, w in zip(probs, want):
             assert torch.equal(p, w)
+    # a long list takes the path with one enqueuing host thread per stream
+    long_reqs, long_want = reqs * 4, want * 4
+    pool = rec.StreamPool(3)
+    assert len(long_reqs) >= 8 * 3
+    long_probs = [torch.zeros(r.B, dtype=torch.float32, device="cuda") for r in long_reqs]
+    torch.cuda.synchronize()
+    for _ in range(2):
+        rec.ForwardMany(model, long_reqs, long_probs, pool.streams).launch()
+    pool.synchronize()
+    for p, w in zip(long_probs, long_want):
+        assert torch.equal(p, w)
     # against the oracle as well
     sub = cfg.replace(B=sum(sizes))
     hb = workload.slice_batch(batch, cfg.T, 0, sum(sizes))
