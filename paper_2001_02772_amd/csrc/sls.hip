@@ -90,6 +90,49 @@ __global__ __launch_bounds__(SLS_WAVES_PER_BLOCK* REC_WAVE) void sls_kernel(
         *reinterpret_cast<float4*>(out + (int64_t)b * stride_b + (int64_t)t * stride_t + col) = acc;
 }
 
+// Bags of one or two lookups (the one-hot "Concat" models of Table I): a wavefront per bag
+// would leave most lanes idle, so here each group of LPR lanes owns a bag of its own and a
+// wavefront pools 64/LPR bags at once, rows added in index order.  Correct for any length;
+// chosen by the host when the average bag is at most two lookups long.
+template <int LPR>
+__global__ __launch_bounds__(SLS_WAVES_PER_BLOCK* REC_WAVE) void sls_short_kernel(
+    const float* const* __restrict__ tables, const int32_t* __restrict__ indices,
+    const int64_t* __restrict__ off, int64_t n_bags, int32_t B, int32_t D, float* __restrict__ out,
+    int64_t stride_b, int64_t stride_t) {
+    constexpr int G = REC_WAVE / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane / LPR;
+    const int col = (lane % LPR) * 4;
+    const int64_t bag = ((int64_t)blockIdx.x * SLS_WAVES_PER_BLOCK + wave) * G + sub;
+    if (bag >= n_bags || col >= D) return;              // no cross-lane traffic below
+    const int32_t t = (int32_t)(bag / B);
+    const int32_t b = (int32_t)(bag - (int64_t)t * B);
+    const float* __restrict__ tab = tables[t];
+    const int64_t beg = off[bag];
+    const int32_t L = (int32_t)(off[bag + 1] - beg);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t j = 0; j < L; j += U) {
+        int32_t idx[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) idx[u] = (j + u < L) ? indices[beg + j + u] : -1;
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx[u] >= 0) v[u] = *reinterpret_cast<const float4*>(tab + (int64_t)idx[u] * D + col);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc.x += v[u].x;
+            acc.y += v[u].y;
+            acc.z += v[u].z;
+            acc.w += v[u].w;
+        }
+    }
+    *reinterpret_cast<float4*>(out + (int64_t)b * stride_b + (int64_t)t * stride_t + col) = acc;
+}
+
 // ------------------------------------------------------------------ validator
 // res[0] = sum of lengths, res[1] = 1 if any length < 0,
 // res[2] = number of out-of-range indices, res[3] = position of the first one.
@@ -209,9 +252,27 @@ static int sls_xcd_remap_default() {
 }
 
 static rec_status rec_sls_launch(const float* const* tables, int32_t T, int32_t D, const int32_t* indices,
-                          const int64_t* offsets, int32_t B, float* out, int64_t stride_b,
+                          int64_t n_indices, const int64_t* offsets, int32_t B, float* out, int64_t stride_b,
                           int64_t stride_t, hipStream_t s) {
     const int64_t n_bags = (int64_t)T * B;
+    if (n_indices <= 2 * n_bags) {
+        // short bags: several bags per wavefront
+#define SLS_SHORT(LPR)                                                                                        \
+    do {                                                                                                      \
+        const int64_t per_block = (int64_t)SLS_WAVES_PER_BLOCK * (REC_WAVE / LPR);                            \
+        const int64_t blocks = (n_bags + per_block - 1) / per_block;                                          \
+        hipLaunchKernelGGL((sls_short_kernel<LPR>), dim3((unsigned)blocks), dim3(SLS_WAVES_PER_BLOCK* REC_WAVE), 0, s, \
+                           tables, indices, offsets, n_bags, B, D, out, stride_b, stride_t);                  \
+    } while (0)
+        if (D <= 16) SLS_SHORT(4);
+        else if (D <= 32) SLS_SHORT(8);
+        else if (D <= 64) SLS_SHORT(16);
+        else if (D <= 128) SLS_SHORT(32);
+        else SLS_SHORT(64);
+#undef SLS_SHORT
+        REC_CHECK_LAUNCH();
+        return REC_OK;
+    }
     const int64_t blocks = (n_bags + SLS_WAVES_PER_BLOCK - 1) / SLS_WAVES_PER_BLOCK;
     if (blocks > 2147483647LL) return REC_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)blocks), block(SLS_WAVES_PER_BLOCK * REC_WAVE);
@@ -274,7 +335,7 @@ rec_status rec_sls_forward_step(const float* const* tables, const int64_t* rows,
         st = launch_offsets(lengths, (int64_t)T * B, w.offsets, s);
         if (st != REC_OK) return st;
     }
-    return rec_sls_launch(tables, T, D, indices, w.offsets, B, out, out_stride_b, out_stride_t, s);
+    return rec_sls_launch(tables, T, D, indices, n_indices, w.offsets, B, out, out_stride_b, out_stride_t, s);
 }
 
 extern "C" {
@@ -294,7 +355,7 @@ rec_status rec_sls_forward_offsets(const float* const* tables, const int64_t* ro
     if (out_stride_b < 0 || out_stride_t < 0 || out_stride_b % 4 || out_stride_t % 4 || !rec_aligned(out, 16) ||
         !rec_aligned(offsets, 8))
         return REC_ERR_BAD_SHAPE;
-    return rec_sls_launch(tables, T, D, indices, offsets, B, out, out_stride_b, out_stride_t,
+    return rec_sls_launch(tables, T, D, indices, n_indices, offsets, B, out, out_stride_b, out_stride_t,
                           static_cast<hipStream_t>(stream));
 }
 

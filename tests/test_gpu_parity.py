@@ -106,6 +106,29 @@ def test_sls_ragged_vs_oracle(rec, D):
     assert np.all(np.abs(got.astype(np.float64) - E) <= (L + 1) * 2.0**-24 * aabs + 1e-30)
 
 
+@pytest.mark.parametrize("D", [4, 16, 32, 48, 64, 128, 256])
+def test_sls_short_bags_vs_oracle(rec, D):
+    """Average bag length <= 2 takes the kernel that pools several bags per wavefront; one long
+    bag among them must still come out right."""
+    T, B, R = 3, 400, 300
+    tables = [rng.uniform(-0.05, 0.05, size=(R, D)).astype(np.float32) for _ in range(T)]
+    lengths = rng.integers(0, 4, size=T * B).astype(np.int32)
+    lengths[7] = 200
+    lengths[T * B - 1] = 3
+    assert lengths.sum() <= 2 * T * B
+    idx = rng.integers(0, R, size=int(lengths.sum())).astype(np.int32)
+    E, _, aabs = oracle.sls(tables, idx, lengths, B, extra=True)
+    got = rec.sls_forward(rec.Tables([dev(t) for t in tables]), dev(idx), dev(lengths), B).cpu().numpy()
+    assert_close(got, E, TOL_F32, f"short-bag SLS D={D}")
+    L = lengths.reshape(T, B).T[:, :, None]
+    assert np.all(np.abs(got.astype(np.float64) - E) <= (L + 1) * 2.0**-24 * aabs + 1e-30)
+    # one lookup per bag is a gather, exactly
+    idx1 = rng.integers(0, R, size=T * B).astype(np.int32)
+    got1 = rec.sls_forward(rec.Tables([dev(t) for t in tables]), dev(idx1), dev(np.ones(T * B, np.int32)), B).cpu().numpy()
+    for t in range(T):
+        assert np.array_equal(got1[:, t, :], tables[t][idx1[t * B:(t + 1) * B]])
+
+
 def test_sls_integer_tables_exact_and_special_lengths(rec):
     T, B, R, D = 4, 50, 64, 32
     tables = [rng.integers(-8, 9, size=(R, D)).astype(np.float32) for _ in range(T)]
