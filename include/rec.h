@@ -157,7 +157,10 @@ rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int32_t D,
  * dense features themselves when n_bottom = 0 (bottom_widths = {F}, bottom_W/b unused);
  * E_t = pooled embedding of table t.  x's width must be a multiple of 4.
  * The handle BORROWS every pointer in the descriptor: DEV memory must stay
- * alive and unchanged while the handle is used; HOST arrays are copied. */
+ * alive and unchanged while the handle is used; HOST arrays are copied.
+ * rec_model_create may allocate device memory of its own (a copy of the first top
+ * layer's weights with rows padded to a multiple of 16 bytes when the interaction
+ * width is not one; synchronises the device once); rec_model_destroy frees it. */
 typedef enum { REC_INTERACT_DOT = 0, REC_INTERACT_CONCAT = 1 } rec_interaction;
 
 typedef struct {

@@ -24,7 +24,8 @@ constexpr int IT_THREADS = 256;
 // split the 16x16 tiles of the lower triangle (ti >= tj) between them round-robin.
 template <int SPB>
 __global__ __launch_bounds__(IT_THREADS) void interact_mfma_kernel(const float* __restrict__ vecs, int32_t B, int32_t V,
-                                                                   int32_t D, float* __restrict__ out, int64_t ldo) {
+                                                                   int32_t D, float* __restrict__ out, int64_t ldo,
+                                                                   int32_t zero_to) {
     extern __shared__ __attribute__((aligned(16))) float sm[];
     constexpr int WPS = 4 / SPB;                       // waves per sample
     constexpr int TPS = WPS * 64;                      // threads per sample
@@ -59,6 +60,8 @@ __global__ __launch_bounds__(IT_THREADS) void interact_mfma_kernel(const float* 
     __syncthreads();
     if (!active) return;
     for (int d = tsub; d < D; d += TPS) o[d] = my[d];
+    // columns behind the packed triangle that the consumer reads as padding of its k range
+    for (int c = D + V * (V - 1) / 2 + tsub; c < zero_to; c += TPS) o[c] = 0.f;
 
     // Z = V V^T on 16x16 tiles.  Lane (row l%16, q = l/16) owns k = 4q..4q+3 of each 16-wide k chunk
     // and feeds them to 4 MFMAs, one component each; both operands use the same k assignment.
@@ -94,7 +97,13 @@ __global__ __launch_bounds__(IT_THREADS) void interact_mfma_kernel(const float* 
 
 extern "C" rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int32_t D, float* out, int64_t ldo,
                                    void* stream) {
+    return rec_interact_padded(vecs, B, V, D, out, ldo, 0, stream);
+}
+
+rec_status rec_interact_padded(const float* vecs, int32_t B, int32_t V, int32_t D, float* out, int64_t ldo,
+                               int32_t zero_to, void* stream) {
     if (B < 0 || V < 1) return REC_ERR_BAD_SHAPE;
+    if (zero_to > ldo) return REC_ERR_BAD_SHAPE;
     if (V > 128 || D < 4 || D > 256 || D % 4) return REC_ERR_UNSUPPORTED;   // bounds the LDS tile at 130 KB
     if (ldo < (int64_t)D + (int64_t)V * (V - 1) / 2) return REC_ERR_BAD_SHAPE;
     if (B == 0) return REC_OK;
@@ -105,14 +114,14 @@ extern "C" rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int3
     const size_t budget = 64 * 1024;
     if (2 * per_sample <= budget) {
         hipLaunchKernelGGL(interact_mfma_kernel<2>, dim3((unsigned)((B + 1) / 2)), dim3(IT_THREADS), 2 * per_sample, s, vecs,
-                           B, V, D, out, ldo);
+                           B, V, D, out, ldo, zero_to);
     } else {
         // up to 128 x 260 floats = 130 KB for the largest supported shape: needs the opt-in above 64 KB
         static const hipError_t big_lds = hipFuncSetAttribute(reinterpret_cast<const void*>(interact_mfma_kernel<1>),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 136 * 1024);
         if (per_sample > budget && big_lds != hipSuccess) return REC_ERR_DEVICE;
         hipLaunchKernelGGL(interact_mfma_kernel<1>, dim3((unsigned)B), dim3(IT_THREADS), per_sample, s, vecs, B, V, D, out,
-                           ldo);
+                           ldo, zero_to);
     }
     REC_CHECK_LAUNCH();
     return REC_OK;

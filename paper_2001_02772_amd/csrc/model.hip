@@ -16,6 +16,13 @@ struct rec_model {
     std::vector<const float*> bottom_b, top_b;
     rec_dtype dt;
     bool concat;             // predictor input = [bottom output | pooled embeddings]
+    // The dot interaction's width D + T(T+1)/2 is rarely a multiple of the 16 bytes the FC kernels
+    // load at a time (87 for 10 tables of width 32), which would put the first predictor layer on
+    // element-wise loads.  The model then owns a copy of that layer's weights with every row
+    // zero-padded to `top_k0` columns, and the interaction writes zeros into the matching columns.
+    void* top_W0_padded = nullptr;
+    std::vector<int32_t> top_widths_run;   // top_widths with [0] = top_k0
+    int32_t top_k0;
     int64_t ld_inter;        // row stride of the interaction output (dot) or of the joined row (concat)
 };
 
@@ -44,7 +51,7 @@ ModelWorkspace carve(const rec_model* m, int32_t B, void* base) {
     p += rec_round_up((size_t)B * m->ld_inter * sizeof(float), 256);
     w.mlp = p;
     const size_t a = m->bottom_W.empty() ? 0 : rec_mlp_workspace_bytes(m->bottom_widths.data(), (int32_t)m->bottom_W.size(), B, m->dt);
-    const size_t c = rec_mlp_workspace_bytes(m->top_widths.data(), (int32_t)m->top_W.size(), B, m->dt);
+    const size_t c = rec_mlp_workspace_bytes(m->top_widths_run.data(), (int32_t)m->top_W.size(), B, m->dt);
     w.mlp_bytes = a > c ? a : c;
     p += w.mlp_bytes;
     w.total = (size_t)(p - static_cast<char*>(base));
@@ -142,12 +149,41 @@ rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     m->top_b.assign(d->top_b, d->top_b + d->n_top);
     m->dt = d->mlp_dtype;
     m->concat = concat;
-    m->ld_inter = (d->top_widths[0] + 3) / 4 * 4;
+    m->top_widths_run = m->top_widths;
+    const int32_t k0 = d->top_widths[0];
+    const int32_t align = (d->mlp_dtype == REC_BF16) ? 8 : 4;       // elements per 16-byte load
+    m->top_k0 = k0;
+    if (!concat && k0 % align != 0) {
+        const int32_t kp = (k0 + align - 1) / align * align;
+        const size_t elt = (d->mlp_dtype == REC_BF16) ? 2 : 4;
+        const size_t n_out = (size_t)d->top_widths[1];
+        void* padded = nullptr;
+        if (hipMalloc(&padded, n_out * kp * elt) != hipSuccess) {
+            delete m;
+            return REC_ERR_DEVICE;
+        }
+        if (hipMemset(padded, 0, n_out * kp * elt) != hipSuccess ||
+            hipMemcpy2D(padded, kp * elt, d->top_W[0], k0 * elt, k0 * elt, n_out, hipMemcpyDeviceToDevice) != hipSuccess ||
+            hipDeviceSynchronize() != hipSuccess) {
+            (void)hipFree(padded);
+            delete m;
+            return REC_ERR_DEVICE;
+        }
+        m->top_W0_padded = padded;
+        m->top_W[0] = padded;
+        m->top_widths_run[0] = kp;
+        m->top_k0 = kp;
+    }
+    m->ld_inter = (m->top_k0 + 3) / 4 * 4;
     *out = m;
     return REC_OK;
 }
 
-void rec_model_destroy(rec_model* m) { delete m; }
+void rec_model_destroy(rec_model* m) {
+    if (!m) return;
+    if (m->top_W0_padded) (void)hipFree(m->top_W0_padded);
+    delete m;
+}
 
 size_t rec_model_workspace_bytes(const rec_model* m, int32_t B_max) {
     if (!m || B_max < 0) return 0;
@@ -209,9 +245,9 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
     st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
                               (int64_t)V * D, D, w.sls, w.sls_bytes, stream, REC_SLS_POOL_ONLY);
     if (st != REC_OK) return st;
-    st = rec_interact(w.vecs, B, V, D, w.inter, m->ld_inter, stream);
+    st = rec_interact_padded(w.vecs, B, V, D, w.inter, m->ld_inter, m->top_k0, stream);
     if (st != REC_OK) return st;
-    return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths.data(), (int32_t)m->top_W.size(), m->dt,
+    return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths_run.data(), (int32_t)m->top_W.size(), m->dt,
                            REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, m->ld_inter, prob, 1, B, w.mlp, w.mlp_bytes, stream);
 }
 

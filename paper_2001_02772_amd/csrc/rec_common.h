@@ -86,6 +86,11 @@ rec_status rec_sls_forward_step(const float* const* tables, const int64_t* rows,
                                 void* stream, rec_sls_step step);
 int64_t* rec_sls_workspace_offsets(void* workspace);
 
+// rec_interact that also writes zeros into columns [D + V(V-1)/2, zero_to) of every output row
+// (zero_to <= ldo): padding for a consumer whose k range is rounded up for alignment.
+rec_status rec_interact_padded(const float* vecs, int32_t B, int32_t V, int32_t D, float* out, int64_t ldo,
+                               int32_t zero_to, void* stream);
+
 // ---- large bf16 layers (gemm_bf16.hip) --------------------------------------------------------
 int rec_gemm_bf16_split(int M, int N, int K);                    // 0: kernel does not apply
 size_t rec_gemm_bf16_partial_bytes(int M, int N, int K);         // fp32 partial tiles for the k split
