@@ -18,6 +18,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X fp32 matrix, published
 
 # HBM bytes per launch of the pooling kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled
 # by a copy-shaped reference dispatch (see profiles/sls_kernel_rmc2_counters.md).  Valid for the
@@ -119,7 +120,13 @@ def cpu_baseline(cfg, batch):
         oracle_forward(cfg, tables, batch, indices=idx)
         singles.append(time.perf_counter() - t0)
     mean = sum(runs) / len(runs)
-    return {"value": batch.B / mean, "unit": "samples/s", "cores": cores, "kind": "oracle",
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+    except OSError:
+        pass
+    return {"value": batch.B / mean, "unit": "samples/s", "cores": cores, "kind": "oracle", "cpu_model": cpu_model,
             "sample": f"one full {cfg.name} batch of {batch.B} samples, whole forward, repeated {len(runs)} times "
                       f"(about 8 s) on {cores} threads; value = mean rate",
             "best_value": batch.B / min(runs),
@@ -162,6 +169,13 @@ def main():
     # time, the latency view) is reported next to it.
     torch.cuda.synchronize()            # set-up (on torch's stream) is complete before the pool's streams start
     sec_single = time_steps(step, a.steps, a.warmup, torch)
+    lat = []                                   # one step at a time, enqueue to completion on the host clock
+    for i in range(a.steps):
+        t0 = time.perf_counter()
+        step(i)
+        torch.cuda.synchronize()
+        lat.append(time.perf_counter() - t0)
+    lat.sort()
     sec = time_many(model, rec, dbs, probs, streams, a.steps, a.warmup, torch) if a.streams > 1 else sec_single
     value = cfg.B / sec
 
@@ -182,6 +196,43 @@ def main():
     roofline = {"bound": "hbm", "kernel": "sls_kernel", "achieved": sls_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": sls_gbs / HBM_PEAK_GBS, "traffic": SLS_COUNTED_TRAFFIC_BYTES.get(cfg.name), "us_per_launch": sls_sec * 1e6,
                 "algorithmic_bytes_per_launch": sls_bytes}
+
+    # compulsory traffic: distinct rows one batch touches (x row bytes), from the generated indices
+    hb = host_batches[0]
+    off = np.concatenate([[0], np.cumsum(hb.lengths, dtype=np.int64)])
+    distinct = int(sum(np.unique(hb.indices[off[t * cfg.B]:off[(t + 1) * cfg.B]]).size for t in range(cfg.T)))
+    roofline["distinct_rows_per_batch"] = distinct
+    roofline["compulsory_row_bytes_per_batch"] = distinct * 4 * cfg.D
+    if roofline["traffic"]:
+        # share of the algorithmic bytes that did not come from HBM (served by L2 / Infinity Cache)
+        roofline["cache_served_fraction"] = 1.0 - roofline["traffic"] / sls_bytes
+        roofline["hbm_gbs_counted"] = roofline["traffic"] / sls_sec / 1e9
+
+    # the two FC stacks timed alone (all their launches between two events): achieved FLOP/s.
+    # (Through rec_mlp_forward with the caller's weights: inside the model the first predictor layer
+    # of a dot-interaction model runs on a copy padded for aligned loads and is faster than here.)
+    def stack_rate(Ws, bs, x, final_act):
+        if not Ws:
+            return None
+        widths = [Ws[0].shape[1]] + [w.shape[0] for w in Ws]
+        wd = rec.BF16 if cfg.bf16 else rec.F32
+        y = torch.empty((cfg.B, widths[-1]), dtype=torch.float32, device="cuda")
+        wsb = torch.empty(max(256, rec.mlp_workspace_bytes(widths, cfg.B, wd)), dtype=torch.uint8, device="cuda")
+        sec_ = event_time(lambda i: rec.mlp_forward(Ws, bs, x, rec.ACT_RELU, final_act, wdtype=wd, y=y, ldy=widths[-1],
+                                                    workspace=wsb), a.steps, a.warmup, torch)
+        fl = 2.0 * cfg.B * sum(widths[l] * widths[l + 1] for l in range(len(Ws)))
+        return {"widths": widths, "us": sec_ * 1e6, "flops": fl, "tflops": fl / sec_ / 1e12}
+
+    peak_tf = MFMA_BF16_PEAK_TFLOPS if cfg.bf16 else MFMA_F32_PEAK_TFLOPS
+    stacks = {"bottom": stack_rate(model.bottom_W, model.bottom_b, dbs[0].dense, rec.ACT_RELU),
+              "top": stack_rate(model.top_W, model.top_b,
+                                torch.randn((cfg.B, model.top_W[0].shape[1]), dtype=torch.float32, device="cuda"),
+                                rec.ACT_SIGMOID)}
+    both = [s for s in stacks.values() if s]
+    stacks["total"] = {"us": sum(s["us"] for s in both), "flops": sum(s["flops"] for s in both),
+                       "tflops": sum(s["flops"] for s in both) / sum(s["us"] for s in both) / 1e6,
+                       "peak_tflops": peak_tf,
+                       "frac": sum(s["flops"] for s in both) / sum(s["us"] for s in both) / 1e6 / peak_tf}
 
     sls_roofline = roofline
     if cfg.bf16:
@@ -238,8 +289,9 @@ def main():
                       "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
                       "bottom": list(cfg.bottom), "top": list(cfg.top), "interaction": cfg.interaction,
                       "distinct_batches": len(dbs), "streams": a.streams},
-           "single_stream": {"value": cfg.B / sec_single, "ms_per_step": sec_single * 1e3},
-           "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "setup_s": setup_s}
+           "single_stream": {"value": cfg.B / sec_single, "ms_per_step": sec_single * 1e3,
+                             "latency_ms_median": lat[len(lat) // 2] * 1e3, "latency_ms_min": lat[0] * 1e3},
+           "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "fc_stacks": stacks, "setup_s": setup_s}
     if roofline is not sls_roofline:
         out["sls_roofline"] = sls_roofline
 
