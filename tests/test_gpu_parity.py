@@ -318,6 +318,25 @@ def test_concat_model_create_errors(rec):
     assert e.value.status == rec.ERR_BAD_SHAPE
 
 
+@pytest.mark.parametrize("name,B", [("tiny", 5000), ("tiny", 40000), ("wnd-tiny", 3000)])
+def test_model_forward_large_batch(rec, name, B):
+    """Batches far above the benchmark's: T*B = 320,000 bags is past the scan's parallel tiles, so the
+    scan runs as one block with a carry and gets a launch of its own instead of riding with the
+    dense stack."""
+    from paper_2001_02772_amd import workload
+    import oracle as orc
+    cfg = synth.CONFIGS[name].replace(B=B)
+    tables = _host_model(cfg)
+    model = workload.device_model(cfg, tables=rec.Tables([dev(t) for t in tables]))
+    batch = synth.BatchGenerator(cfg).batch(5)
+    db = workload.DeviceBatch(batch)
+    got = model.forward(db.dense, db.indices, db.lengths, B).cpu().numpy()
+    orc.set_threads(16)
+    want = oracle_forward(cfg, tables, batch)
+    orc.set_threads(1)
+    assert_close(got, want, TOL_F32, f"large-batch model {name} B={B}")
+
+
 def test_model_edge_cases(rec):
     from paper_2001_02772_amd import workload
     cfg = synth.CONFIGS["tiny"].replace(R=100)
