@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of 256 MiB (reference dispatches for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--h2d", action="store_true",
+                    help="also time the steps with every batch's inputs copied from pinned host memory")
     ap.add_argument("--sched", action="store_true",
                     help="also tune the request batch size by hill climbing on latency-bounded throughput")
     ap.add_argument("--sweep", action="store_true",
@@ -320,6 +322,9 @@ def main():
     if a.sweep:
         out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
 
+    if a.h2d:
+        out["h2d_inclusive"] = h2d_inclusive(cfg, model, host_batches, streams, a.steps, a.warmup, torch)
+
     if a.sched:
         out["batch_size_tuning"] = batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
                                                      pool_streams=streams if a.streams > 1 else None)
@@ -372,6 +377,42 @@ def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np):
 
 # p95 latency targets per model, ms (Table II, "medium"); low / high = 0.5x / 1.5x (Section V)
 TABLE_II_TARGET_MS = {"rmc1": 100.0, "rmc2": 400.0, "rmc2-uniform": 400.0, "rmc3": 100.0}
+
+
+def h2d_inclusive(cfg, model, host_batches, streams, steps, warmup, torch):
+    """The same steps with every batch's inputs (dense, indices, lengths) copied from pinned host
+    memory on the stream that then runs the forward: the rate a caller with host-resident inputs
+    sees.  Never the headline value."""
+    ext = [torch.cuda.ExternalStream(s.cuda_stream) for s in streams]
+    pinned = [(torch.from_numpy(b.dense).pin_memory(), torch.from_numpy(b.indices).pin_memory(),
+               torch.from_numpy(b.lengths).pin_memory()) for b in host_batches]
+    n_max = max(b.indices.size for b in host_batches)
+    slots = [(torch.empty((cfg.B, cfg.F), dtype=torch.float32, device="cuda"),
+              torch.empty(n_max, dtype=torch.int32, device="cuda"),
+              torch.empty(cfg.T * cfg.B, dtype=torch.int32, device="cuda"),
+              torch.empty(cfg.B, dtype=torch.float32, device="cuda"),
+              torch.empty(model.workspace_bytes(cfg.B), dtype=torch.uint8, device="cuda")) for _ in ext]
+    nbytes = sum(d.numel() * 4 + i.numel() * 4 + l.numel() * 4 for d, i, l in pinned) / len(pinned)
+
+    def run(n):
+        for i in range(n):
+            k = i % len(ext)
+            d, ix, ln = pinned[i % len(pinned)]
+            dd, di, dl, prob, ws = slots[k]
+            with torch.cuda.stream(ext[k]):
+                dd.copy_(d, non_blocking=True)
+                di[: ix.numel()].copy_(ix, non_blocking=True)
+                dl.copy_(ln, non_blocking=True)
+                model.forward(dd, di[: ix.numel()], dl, cfg.B, prob=prob, workspace=ws)
+
+    run(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    return {"value": cfg.B / sec, "unit": "samples/s", "ms_per_step": sec * 1e3, "host_bytes_per_step": nbytes,
+            "host_to_device_gbs": nbytes / sec / 1e9}
 
 
 def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
