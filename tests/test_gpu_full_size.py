@@ -49,3 +49,34 @@ def test_full_size_model_and_sls(rec, name):
     e = assert_close(got, want, TOL_BF16 if cfg.bf16 else TOL_F32, f"{name} model")
     print(f"[full-size] {name}: max rel err {e:.3e}", flush=True)
     oracle.set_threads(1)
+
+
+@pytest.mark.parametrize("name", ["rmc2", "rmc3"])
+def test_full_size_throughput_mode(rec, name):
+    """The launch configuration the benchmark times: requests enqueued by one
+    rec_model_forward_many call over a four-stream pool.  Every output of every request equals
+    the single-stream forward bit for bit, and one batch is checked against the oracle in full."""
+    import oracle
+    from paper_2001_02772_amd import workload
+    pool = rec.StreamPool(4)
+    cfg = synth.CONFIGS[name]
+    print(f"[full-size many] {name}: building model", flush=True)
+    model = workload.device_model(cfg)
+    gen = synth.BatchGenerator(cfg)
+    batches = [gen.batch(k) for k in (1, 2, 3)]
+    dbs = [workload.DeviceBatch(b) for b in batches]
+    single = [model.forward(d.dense, d.indices, d.lengths, cfg.B).clone() for d in dbs]
+    reqs = [dbs[i % 3] for i in range(36)]                       # 36 >= 8 * 4: one enqueuing thread per stream
+    probs = [torch.zeros(cfg.B, dtype=torch.float32, device="cuda") for _ in reqs]
+    torch.cuda.synchronize()
+    print(f"[full-size many] {name}: forward_many", flush=True)
+    rec.ForwardMany(model, reqs, probs, pool.streams).launch()
+    pool.synchronize()
+    for i, p in enumerate(probs):
+        assert torch.equal(p, single[i % 3]), i
+    print(f"[full-size many] {name}: oracle", flush=True)
+    oracle.set_threads(16)
+    small_tables, idx = compact_tables(cfg, batches[1])
+    want = oracle_forward(cfg, small_tables, batches[1], indices=idx)
+    oracle.set_threads(1)
+    assert_close(probs[1].cpu().numpy(), want, TOL_BF16 if cfg.bf16 else TOL_F32, f"{name} forward_many")
