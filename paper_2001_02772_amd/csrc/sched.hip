@@ -1,10 +1,11 @@
 // Query serving around the model forward: request service times, the single-device FIFO queue,
-// latency-bounded throughput, the batch-size hill climb, and an open-loop trace replay on the GPU.
+// latency-bounded throughput, the batch-size hill climb, an open-loop trace replay on the GPU, and
+// the stream pool / throughput-mode entry point that keep several requests in flight.
 //
 // DeepRecSys paper: Section III-C (Poisson arrivals, query sizes), Section IV-A (a query is split
 // into requests of a batch size), Section III-B (throughput is the query rate sustained under a
 // p95 latency target), Section IV-C (the batch size is found by hill climbing on that rate).
-// Everything here is host code except the replay, which drives rec_model_forward.
+// Everything here is host code; the replay and the throughput mode drive rec_model_forward.
 #include <algorithm>
 #include <chrono>
 #include <cmath>
