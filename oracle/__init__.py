@@ -208,3 +208,27 @@ def max_qps(unit_arrival, service, p: float, sla: float, iters: int = 40) -> flo
 def hill_climb(qps) -> int:
     qps = _f64(qps)
     return lib().orc_hill_climb(_p(qps), qps.size)
+
+
+def _i64(v):
+    return np.ascontiguousarray(v, dtype=np.int64)
+
+
+def two_tier_latencies(arrival, size, tau: int, B: int, c, k: int, g):
+    """Latencies with queries of size >= tau on the accelerator (service g[size]) and the rest cut
+    into requests of B on k CPU workers (service c[b])."""
+    arrival, size, c, g = _f64(arrival), _i64(size), _f64(c), _f64(g)
+    assert c.size > B and g.size > (size.max() if size.size else 0)
+    lat = np.empty_like(arrival)
+    lib().orc_two_tier_latencies(_p(arrival), _p(size), C.c_int64(arrival.size), C.c_int64(tau), C.c_int64(B), _p(c),
+                                 C.c_int32(k), _p(g), _p(lat))
+    return lat
+
+
+def two_tier_max_qps(unit_arrival, size, tau: int, B: int, c, k: int, g, p: float, sla: float, iters: int = 40):
+    unit_arrival, size, c, g = _f64(unit_arrival), _i64(size), _f64(c), _f64(g)
+    f = lib().orc_two_tier_max_qps
+    f.restype = C.c_double
+    return f(_p(unit_arrival), _p(size), C.c_int64(size.size), C.c_int64(tau), C.c_int64(B), _p(c), C.c_int32(k), _p(g),
+             C.c_double(p), C.c_double(sla), C.c_int32(iters))
+

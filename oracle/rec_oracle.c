@@ -378,3 +378,93 @@ int64_t orc_hill_climb(const double* qps, int64_t n_candidates) {
     while (i + 1 < n_candidates && qps[i + 1] >= qps[i]) ++i;
     return i;
 }
+
+/* ------------------------------------------------------------------------
+ * Two tiers: CPU workers and one accelerator (Section IV-B "Leverage parallelism with
+ * specialized hardware", Section IV-C second paragraph).
+ * ---------------------------------------------------------------------- */
+
+/* Queries whose size reaches the threshold tau go whole to the accelerator: one device, first
+ * come first served, g[m] seconds for a query of m items (transfer included).  The others are
+ * cut into requests of batch size B (Section IV-A) that run on k identical CPU workers, one
+ * request per worker at a time (the paper runs one request per core): requests are handed out
+ * in arrival order, each to the worker that is free first, c[b] seconds for a request of b
+ * items; a query is done when its last request is done.  latency = done - arrival.
+ * tau = 1 sends every query to the accelerator (the paper's starting point of the climb),
+ * tau above the largest size sends none.  free_at: scratch, k doubles. */
+static void orc_two_tier_run(const double* arrival, const int64_t* size, int64_t n, int64_t tau, int64_t B,
+                             const double* c, int32_t k, const double* g, double* latency, double* free_at) {
+    double gpu_free = 0.0;
+    for (int32_t w = 0; w < k; ++w) free_at[w] = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t m = size[i];
+        double done = arrival[i];
+        if (m >= tau) {
+            const double start = gpu_free > arrival[i] ? gpu_free : arrival[i];
+            gpu_free = start + g[m];
+            done = gpu_free;
+        } else {
+            for (int64_t first = 0; first < m; first += B) {
+                const int64_t b = (m - first < B) ? m - first : B;
+                int32_t w = 0;
+                for (int32_t j = 1; j < k; ++j)
+                    if (free_at[j] < free_at[w]) w = j;
+                const double start = free_at[w] > arrival[i] ? free_at[w] : arrival[i];
+                free_at[w] = start + c[b];
+                if (free_at[w] > done) done = free_at[w];
+            }
+        }
+        latency[i] = done - arrival[i];
+    }
+}
+
+void orc_two_tier_latencies(const double* arrival, const int64_t* size, int64_t n, int64_t tau, int64_t B,
+                            const double* c, int32_t k, const double* g, double* latency) {
+    double* free_at = (double*)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    orc_two_tier_run(arrival, size, n, tau, B, c, k, g, latency, free_at);
+    free(free_at);
+}
+
+static int orc_two_tier_ok(const double* unit_arrival, const int64_t* size, int64_t n, int64_t tau, int64_t B,
+                           const double* c, int32_t k, const double* g, double p, double sla, double rate,
+                           double* arr, double* lat, double* free_at) {
+    for (int64_t i = 0; i < n; ++i) arr[i] = unit_arrival[i] / rate;
+    orc_two_tier_run(arr, size, n, tau, B, c, k, g, lat, free_at);
+    return orc_percentile(lat, n, p) <= sla;
+}
+
+/* Latency-bounded throughput of the two tiers for a threshold tau: as orc_max_qps, with the
+ * latencies of orc_two_tier_latencies.  The no-queueing check serves every query on an idle
+ * system (each on its own, arrival 0). */
+double orc_two_tier_max_qps(const double* unit_arrival, const int64_t* size, int64_t n, int64_t tau, int64_t B,
+                            const double* c, int32_t k, const double* g, double p, double sla, int32_t iters) {
+    if (n <= 0) return 0.0;
+    double* arr = (double*)malloc(sizeof(double) * (size_t)n);
+    double* lat = (double*)malloc(sizeof(double) * (size_t)n);
+    double* free_at = (double*)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1));
+    const double zero = 0.0;
+    for (int64_t i = 0; i < n; ++i) orc_two_tier_run(&zero, size + i, 1, tau, B, c, k, g, lat + i, free_at);
+    double result = 0.0;
+    if (orc_percentile(lat, n, p) <= sla) {
+        double lo = 1.0, hi = 1.0;
+#define OK(r) orc_two_tier_ok(unit_arrival, size, n, tau, B, c, k, g, p, sla, (r), arr, lat, free_at)
+        if (OK(1.0)) {
+            hi = 2.0;
+            while (hi < 1e15 && OK(hi)) { lo = hi; hi *= 2.0; }
+        } else {
+            lo = 0.5;
+            while (lo > 1e-15 && !OK(lo)) { hi = lo; lo *= 0.5; }
+        }
+        for (int32_t it = 0; it < iters; ++it) {
+            const double mid = 0.5 * (lo + hi);
+            if (OK(mid)) lo = mid; else hi = mid;
+        }
+#undef OK
+        result = lo;
+    }
+    free(arr);
+    free(lat);
+    free(free_at);
+    return result;
+}
+

@@ -42,6 +42,14 @@ MUTATIONS = {
     "concat_dense_dropped": ("cat[b * Wc + f] = dense[(int64_t)b * X + f];", "cat[b * Wc + f] = 0.0f;"),
     "concat_dense_transposed": ("cat[b * Wc + f] = dense[(int64_t)b * X + f];",
                                 "cat[b * Wc + f] = dense[((int64_t)f * B + b) % ((int64_t)B * X)];"),
+    "two_tier_threshold_exclusive": ("if (m >= tau) {", "if (m > tau) {"),
+    "two_tier_busiest_worker": ("if (free_at[j] < free_at[w]) w = j;", "if (free_at[j] > free_at[w]) w = j;"),
+    "two_tier_done_is_last_request": ("if (free_at[w] > done) done = free_at[w];", "done = free_at[w];"),
+    "two_tier_accelerator_never_queues": ("const double start = gpu_free > arrival[i] ? gpu_free : arrival[i];",
+                                          "const double start = arrival[i];"),
+    "two_tier_request_before_arrival": ("const double start = free_at[w] > arrival[i] ? free_at[w] : arrival[i];",
+                                        "const double start = free_at[w];"),
+    "two_tier_full_batches_only": ("const int64_t b = (m - first < B) ? m - first : B;", "const int64_t b = B;"),
     "hill_climb_stops_on_ties": ("qps[i + 1] >= qps[i]", "qps[i + 1] > qps[i]"),
     "hill_climb_global_max": ("while (i + 1 < n_candidates && qps[i + 1] >= qps[i]) ++i;",
                               "for (int64_t j = 1; j < n_candidates; ++j) if (qps[j] > qps[i]) i = j;"),

@@ -131,3 +131,104 @@ def test_unit_poisson_arrivals():
     gaps = np.diff(a)
     assert np.all(gaps > 0) and abs(gaps.mean() - 1) < 0.01 and abs(gaps.std() - 1) < 0.01
     assert np.array_equal(a, synth.unit_poisson_arrivals(11, 200_000))
+
+
+# ---- two tiers: CPU workers + accelerator (Section IV-B) ---------------------------------
+
+def _tables(max_n=64, B=8):
+    c = np.concatenate([[0.0], 0.3 + 0.05 * np.arange(1, B + 1)])        # CPU request of b items
+    g = np.concatenate([[0.0], 0.6 + 0.004 * np.arange(1, max_n + 1)])   # accelerator, query of m items
+    return c, g
+
+
+def test_two_tier_hand_example(golden):
+    g = golden("two_tier_hand_example.txt")
+    lat = oracle.two_tier_latencies(g["arrival"], np.array(g["size"], np.int64), int(g["tau"][0]), int(g["batch"][0]),
+                                    g["c"], int(g["k"][0]), g["g"])
+    assert np.allclose(lat, g["latency"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(np.array(g["arrival"]) + lat, g["finish"], rtol=1e-12, atol=1e-12)
+
+
+def test_two_tier_reduces_to_single_queues():
+    n, B = 400, 8
+    c, g = _tables(64, B)
+    a = np.cumsum(rng.exponential(0.5, n))
+    size = rng.integers(1, 65, n)
+    # threshold 1: everything on the accelerator = the FIFO queue with service g[size]
+    assert np.array_equal(oracle.two_tier_latencies(a, size, 1, B, c, 3, g), oracle.fifo_latencies(a, g[size]))
+    # no accelerator traffic, one worker: the FIFO queue whose service is the query's requests back to back
+    svc = np.array([oracle.query_service(int(m), B, c) for m in size])
+    assert np.allclose(oracle.two_tier_latencies(a, size, 10**9, B, c, 1, g), oracle.fifo_latencies(a, svc), rtol=1e-12)
+    # plenty of workers: no waiting, a query takes as long as its longest request
+    lat = oracle.two_tier_latencies(a, size, 10**9, B, c, 10_000, g)
+    assert np.allclose(lat, np.where(size >= B, c[B], c[np.minimum(size, B)]), rtol=1e-12)
+    # the threshold is inclusive: a query of exactly tau items goes to the accelerator
+    one = oracle.two_tier_latencies([0.0], [16], 16, B, c, 2, g)
+    assert one[0] == g[16]
+    assert oracle.two_tier_latencies([0.0], [15], 16, B, c, 2, g)[0] == c[8]      # 8 + 7 items on two idle workers
+
+
+def test_two_tier_vs_event_driven_simulation():
+    import heapq
+    from collections import deque
+    n, B, k, tau = 300, 8, 3, 40
+    c, g = _tables(64, B)
+    a = np.cumsum(rng.exponential(0.35, n))
+    size = rng.integers(1, 65, n)
+    # independent formulation: a clock walks through arrival and completion events; pending CPU
+    # requests wait in one FIFO queue and idle workers pull from it; the accelerator has its own queue
+    events = [(float(a[i]), 1, "arr", i) for i in range(n)]           # completions (0) before arrivals (1) at equal times
+    heapq.heapify(events)
+    cpu_q, gpu_q, idle, gpu_idle = deque(), deque(), k, True
+    left = np.zeros(n, np.int64)
+    done = np.zeros(n)
+    while events:
+        now, _, kind, i = heapq.heappop(events)
+        if kind == "arr":
+            m = int(size[i])
+            if m >= tau:
+                gpu_q.append(i)
+            else:
+                parts = [B] * (m // B) + ([m % B] if m % B else [])
+                left[i] = len(parts)
+                cpu_q.extend((i, b) for b in parts)
+        elif kind == "cpu":
+            idle += 1
+            left[i] -= 1
+            if left[i] == 0:
+                done[i] = now
+        else:
+            gpu_idle = True
+            done[i] = now
+        while idle and cpu_q:
+            q, b = cpu_q.popleft()
+            idle -= 1
+            heapq.heappush(events, (now + c[b], 0, "cpu", q))
+        if gpu_idle and gpu_q:
+            q = gpu_q.popleft()
+            gpu_idle = False
+            heapq.heappush(events, (now + g[size[q]], 0, "gpu", q))
+    lat = oracle.two_tier_latencies(a, size, tau, B, c, k, g)
+    assert np.allclose(lat, done - a, rtol=1e-10, atol=1e-12)
+    # more workers never make any query later
+    more = oracle.two_tier_latencies(a, size, tau, B, c, k + 1, g)
+    assert np.all(more <= lat + 1e-12)
+
+
+def test_two_tier_max_qps():
+    n, B = 500, 8
+    c, g = _tables(64, B)
+    unit = synth.unit_poisson_arrivals(5, n)
+    size = rng.integers(1, 65, n)
+    # all on the accelerator: the single-queue search on g[size], bit for bit
+    for sla in (0.5, 0.9, 3.0):
+        assert oracle.two_tier_max_qps(unit, size, 1, B, c, 4, g, 0.95, sla) == oracle.max_qps(unit, g[size], 0.95, sla)
+    # boundary of feasibility, and more CPU workers never lower the rate
+    sla = 1.5
+    r4 = oracle.two_tier_max_qps(unit, size, 40, B, c, 4, g, 0.95, sla)
+    assert r4 > 0
+    ok = lambda r, k: oracle.percentile(oracle.two_tier_latencies(unit / r, size, 40, B, c, k, g), 0.95) <= sla
+    assert ok(r4, 4) and not ok(r4 * 1.001, 4)
+    assert oracle.two_tier_max_qps(unit, size, 40, B, c, 8, g, 0.95, sla) >= r4
+    # a target below what an idle system delivers
+    assert oracle.two_tier_max_qps(unit, size, 40, B, c, 4, g, 0.95, 0.2) == 0.0
