@@ -328,6 +328,9 @@ def main():
     if a.sched:
         out["batch_size_tuning"] = batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
                                                      pool_streams=streams if a.streams > 1 else None)
+        if not a.no_cpu_baseline:
+            out["offload_threshold_tuning"] = offload_threshold_tuning(
+                cfg, out["batch_size_tuning"]["service_table_s"], gen, torch, rec, synth, workload, np)
 
     if not a.no_cpu_baseline:
         base, p_cpu = cpu_baseline(cfg, host_batches[0])
@@ -444,7 +447,8 @@ def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
     del singles
 
     cands = [1 << k for k in range(11)]
-    res = {"service_us": {str(b): table[b] * 1e6 for b in (1, 16, 64, 256, 1024)}, "percentile": 0.95,
+    res = {"service_us": {str(b): table[b] * 1e6 for b in (1, 16, 64, 256, 1024)}, "service_table_s": table.tolist(),
+           "percentile": 0.95,
            "candidates": cands, "targets": {}}
 
     def tune(n_queries, targets):
@@ -499,6 +503,93 @@ def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
     if pool_streams is not None:
         res["live_hill_climb"] = {f"{t}ms": live_hill_climb(cfg, model, gen, sizes, unit, t * 1e-3, cands, pool_streams,
                                                             rec, workload, np) for t in (1.0, 5.0)}
+    return res
+
+
+def cpu_request_table(cfg, gen, synth, workload, np, max_b=1024):
+    """CPU-baseline leg: seconds for one request of b items on ONE host core, from the oracle run
+    single-threaded on slices of a batch (b = 1, 2, 4, ..., linear in between)."""
+    import oracle
+    src = gen.batch(300, B=max_b)
+    pb, pt = synth.mlp_params(cfg.bottom, 0), synth.mlp_params(cfg.top, 1)
+    oracle.set_threads(1)
+    grid, t = [], []
+    b = 1
+    while b <= max_b:
+        part = workload.slice_batch(src, cfg.T, 0, b)
+        tables, idx = synth.compact_tables(cfg.replace(B=b), part)
+        best = 1e30
+        for _ in range(3 if b <= 64 else 1):
+            t0 = time.perf_counter()
+            st, _ = oracle.model_forward(tables, pb.W, pb.b, pt.W, pt.b, part.dense, idx, part.lengths, bf16=cfg.bf16,
+                                         concat=cfg.interaction == "concat")
+            best = min(best, time.perf_counter() - t0)
+            assert st == oracle.OK
+        grid.append(b)
+        t.append(best)
+        b *= 2
+    table = np.zeros(max_b + 1)
+    table[1:] = np.interp(np.arange(1, max_b + 1), grid, t)
+    return table
+
+
+def offload_threshold_tuning(cfg, gpu_table, gen, torch, rec, synth, workload, np, n_queries=20_000):
+    """Second hill climb of Section IV-C on the two-tier queueing model (Section IV-B): queries of
+    tau items or more go to the device (service = measured request time + host-to-device copy of
+    the query's inputs), the others are split into requests on the host's cores (request time =
+    the oracle on one core: the only CPU implementation there is, a stand-in for a CPU serving
+    path this library does not have).  Model only: no query is served on the CPU."""
+    cores = min(16, os.cpu_count() or 1)
+    c = cpu_request_table(cfg, gen, synth, workload, np)
+    # host-to-device: one pinned copy of a full batch's inputs, and of a one-item batch
+    big = gen.batch(301, B=1000)
+    per_item = (big.dense.nbytes + big.indices.nbytes + big.lengths.nbytes) / 1000.0
+    src = torch.empty(int(per_item * 1000), dtype=torch.uint8).pin_memory()
+    dst = torch.empty_like(src, device="cuda")
+
+    def copy_s(nbytes, reps=50):
+        dst[:nbytes].copy_(src[:nbytes], non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            dst[:nbytes].copy_(src[:nbytes], non_blocking=True)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+    t_small, t_big = copy_s(int(per_item)), copy_s(int(per_item * 1000))
+    m = np.arange(0, 1001)
+    g = np.asarray(gpu_table)[:1001] + t_small + (t_big - t_small) * (m - 1) / 999.0
+    g[0] = 0.0
+
+    sizes = synth.lognormal_query_sizes(synth.MASTER_SEED, n_queries)
+    unit = synth.unit_poisson_arrivals(synth.MASTER_SEED, n_queries)
+    medium = TABLE_II_TARGET_MS.get(cfg.name, 100.0)
+    res = {"cpu_workers": cores, "queries": n_queries,
+           "cpu_request_ms": {str(b): c[b] * 1e3 for b in (1, 16, 64, 256, 1024)},
+           "device_query_ms_with_copy": {str(b): g[b] * 1e3 for b in (1, 16, 64, 256, 1000)}, "targets": {}}
+    batches = [1 << i for i in range(11)]
+    taus = [1 << i for i in range(11)] + [1001]                    # 1001: nothing goes to the device
+    for sla in (0.5 * medium, medium):
+        s = sla * 1e-3
+        # first climb: request batch size for the CPU tier alone
+        cpu_qps = []
+        for B in batches:
+            cpu_qps.append(rec.sched_two_tier_max_qps(unit, sizes, 1001, B, c, cores, g, 0.95, s, 30))
+            if len(cpu_qps) > 1 and cpu_qps[-1] < cpu_qps[-2]:
+                break
+        kb = rec.sched_hill_climb(cpu_qps)
+        B = batches[kb]
+        # second climb: query-size threshold, from "everything on the device" upwards
+        qps = []
+        for tau in taus:
+            qps.append(rec.sched_two_tier_max_qps(unit, sizes, tau, B, c, cores, g, 0.95, s, 30))
+            if len(qps) > 1 and qps[-1] < qps[-2]:
+                break
+        kt = rec.sched_hill_climb(qps)
+        res["targets"][f"{sla:g}ms"] = {"cpu_batch": B, "cpu_only_max_qps": {str(b): q for b, q in zip(batches, cpu_qps)},
+                                        "max_qps_by_threshold": {str(t): q for t, q in zip(taus, qps)},
+                                        "chosen_threshold": taus[kt], "chosen_max_qps": qps[kt]}
+        print(f"[sched] threshold climb, target {sla:g} ms: cpu batch {B}, threshold {taus[kt]}, {qps[kt]:.0f} queries/s",
+              file=sys.stderr, flush=True)
     return res
 
 

@@ -232,6 +232,27 @@ double rec_sched_max_qps(const double* unit_arrival, const double* service, int6
  * -1 if n_candidates < 1 or qps is NULL. */
 int64_t rec_sched_hill_climb(const double* qps, int64_t n_candidates);
 
+/* Two tiers (Section IV-B, "Leverage parallelism with specialized hardware"; Section IV-C,
+ * second hill climb): queries of tau items or more go whole to the accelerator -- one device,
+ * first come first served, g[m] seconds for a query of m items, transfer included -- and the
+ * others are cut into requests of `batch` items that run on k identical CPU workers: requests are
+ * handed out in arrival order, each to the worker that is free first, c[b] seconds for a request
+ * of b items; a query is done when its last request is.  tau = 1 sends everything to the
+ * accelerator (where the paper's climb starts), tau above the largest size sends nothing.
+ * These two calls are the scheduler's queueing model only: nothing here runs a model on the CPU.
+ * HOST arrays: arrival (non-decreasing) / unit_arrival, size int64 [n] (each >= 0), c [batch+1],
+ * g [max size + 1], latency [n].  size_max = length of g minus 1 (sizes above it are an error). */
+rec_status rec_sched_two_tier_latencies(const double* arrival, const int64_t* size, int64_t n, int64_t tau,
+                                        int64_t batch, const double* c, int32_t k, const double* g, int64_t size_max,
+                                        double* latency);
+
+/* Largest rate r with the p-th percentile of the two-tier latencies (arrivals unit_arrival / r)
+ * <= sla; search as rec_sched_max_qps; 0 if the percentile on an idle system (every query served
+ * alone) already exceeds sla.  NaN on bad arguments. */
+double rec_sched_two_tier_max_qps(const double* unit_arrival, const int64_t* size, int64_t n, int64_t tau, int64_t batch,
+                                  const double* c, int32_t k, const double* g, int64_t size_max, double p, double sla,
+                                  int32_t iters);
+
 /* One request = one rec_model_forward call: inputs as for rec_model_forward (all DEV). */
 typedef struct {
     const float* dense;

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <functional>
 #include <limits>
 #include <new>
 #include <thread>
@@ -50,6 +51,53 @@ struct RateTest {
         return nearest_rank(lat, p) <= sla;    // nth_element reorders lat, which is rewritten next time
     }
 };
+
+// Two-tier queue: the accelerator is one FIFO server; CPU requests go, in arrival order, to the
+// worker that frees up first (a min-heap of the workers' free times).
+struct TwoTier {
+    const int64_t* size;
+    int64_t n, tau, batch;
+    const double* c;
+    int32_t k;
+    const double* g;
+    std::vector<double> heap;                  // scratch: k free times
+
+    void run(const double* arrival, double* lat) {
+        run_range(arrival, 0, n, lat);
+    }
+    // queries [first, last) on a system that starts idle; arrival/lat are indexed from `first`
+    void run_range(const double* arrival, int64_t first, int64_t last, double* lat) {
+        heap.assign((size_t)k, 0.0);           // all equal: already a heap
+        double device_free = 0.0;
+        for (int64_t q = first; q < last; ++q) {
+            const double at = arrival[q - first];
+            const int64_t m = size[q];
+            double finished = at;
+            if (m >= tau) {
+                device_free = std::max(device_free, at) + g[m];
+                finished = device_free;
+            } else {
+                for (int64_t left = m; left > 0; left -= batch) {
+                    const int64_t b = std::min(left, batch);
+                    std::pop_heap(heap.begin(), heap.end(), std::greater<double>());
+                    const double end = std::max(heap.back(), at) + c[b];
+                    heap.back() = end;
+                    std::push_heap(heap.begin(), heap.end(), std::greater<double>());
+                    finished = std::max(finished, end);
+                }
+            }
+            lat[q - first] = finished - at;
+        }
+    }
+};
+
+bool two_tier_args_ok(const int64_t* size, int64_t n, int64_t tau, int64_t batch, const double* c, int32_t k,
+                      const double* g, int64_t size_max) {
+    if (!size || !c || !g || n < 0 || tau < 0 || batch < 1 || k < 1 || size_max < 0) return false;
+    for (int64_t i = 0; i < n; ++i)
+        if (size[i] < 0 || size[i] > size_max) return false;
+    return true;
+}
 
 }  // namespace
 
@@ -150,6 +198,58 @@ double rec_sched_max_qps(const double* unit_arrival, const double* service, int6
         }
     }
     for (int32_t k = 0; k < iters; ++k) {
+        const double mid = 0.5 * (feasible + infeasible);
+        if (ok(mid)) feasible = mid;
+        else infeasible = mid;
+    }
+    return feasible;
+}
+
+rec_status rec_sched_two_tier_latencies(const double* arrival, const int64_t* size, int64_t n, int64_t tau,
+                                        int64_t batch, const double* c, int32_t k, const double* g, int64_t size_max,
+                                        double* latency) {
+    if (n == 0) return REC_OK;
+    if (!arrival || !latency || !size || !c || !g) return REC_ERR_NULL;
+    if (!two_tier_args_ok(size, n, tau, batch, c, k, g, size_max)) return REC_ERR_BAD_SHAPE;
+    for (int64_t i = 1; i < n; ++i)
+        if (arrival[i] < arrival[i - 1]) return REC_ERR_BAD_SHAPE;
+    TwoTier sim{size, n, tau, batch, c, k, g, {}};
+    sim.run(arrival, latency);
+    return REC_OK;
+}
+
+double rec_sched_two_tier_max_qps(const double* unit_arrival, const int64_t* size, int64_t n, int64_t tau, int64_t batch,
+                                  const double* c, int32_t k, const double* g, int64_t size_max, double p, double sla,
+                                  int32_t iters) {
+    if (!unit_arrival || n < 1 || !(p > 0.0) || p > 1.0 || iters < 0) return kNaN;
+    if (!two_tier_args_ok(size, n, tau, batch, c, k, g, size_max)) return kNaN;
+    TwoTier sim{size, n, tau, batch, c, k, g, {}};
+    std::vector<double> arr((size_t)n), lat((size_t)n);
+    const double zero = 0.0;
+    for (int64_t q = 0; q < n; ++q) sim.run_range(&zero, q, q + 1, &lat[(size_t)q]);   // every query alone on an idle system
+    if (nearest_rank(lat, p) > sla) return 0.0;
+    auto ok = [&](double rate) {
+        for (int64_t i = 0; i < n; ++i) arr[(size_t)i] = unit_arrival[i] / rate;
+        sim.run(arr.data(), lat.data());
+        return nearest_rank(lat, p) <= sla;
+    };
+    double feasible, infeasible;
+    if (ok(1.0)) {
+        feasible = 1.0;
+        infeasible = 2.0;
+        while (infeasible < 1e15 && ok(infeasible)) {
+            feasible = infeasible;
+            infeasible *= 2.0;
+        }
+    } else {
+        infeasible = 1.0;
+        feasible = 0.5;
+        while (feasible > 1e-15 && !ok(feasible)) {
+            infeasible = feasible;
+            feasible *= 0.5;
+        }
+    }
+    for (int32_t it = 0; it < iters; ++it) {
         const double mid = 0.5 * (feasible + infeasible);
         if (ok(mid)) feasible = mid;
         else infeasible = mid;

@@ -32,7 +32,7 @@ EXPORTS = (
     "rec_interact",
     "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
     "rec_sched_query_service", "rec_sched_fifo_latencies", "rec_sched_percentile", "rec_sched_max_qps",
-    "rec_sched_hill_climb", "rec_serve_trace", "rec_serve_trace_many", "rec_model_forward_many",
+    "rec_sched_hill_climb", "rec_sched_two_tier_latencies", "rec_sched_two_tier_max_qps", "rec_serve_trace", "rec_serve_trace_many", "rec_model_forward_many",
     "rec_stream_pool_create", "rec_stream_pool_destroy", "rec_stream_pool_size", "rec_stream_pool_stream",
     "rec_stream_pool_synchronize",
 )
@@ -108,6 +108,10 @@ def lib():
     L.rec_sched_percentile.argtypes = [vp, i64, C.c_double]
     L.rec_sched_max_qps.restype = C.c_double
     L.rec_sched_max_qps.argtypes = [vp, vp, i64, C.c_double, C.c_double, i32]
+    L.rec_sched_two_tier_latencies.restype = C.c_int
+    L.rec_sched_two_tier_latencies.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, vp]
+    L.rec_sched_two_tier_max_qps.restype = C.c_double
+    L.rec_sched_two_tier_max_qps.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, C.c_double, C.c_double, i32]
     L.rec_sched_hill_climb.restype = i64
     L.rec_sched_hill_climb.argtypes = [vp, i64]
     L.rec_stream_pool_create.restype = C.c_int
@@ -369,6 +373,23 @@ def sched_max_qps(unit_arrival, service, p: float, sla: float, iters: int = 40) 
 def sched_hill_climb(qps) -> int:
     qps = _host_f64(qps)
     return lib().rec_sched_hill_climb(qps.ctypes.data, qps.size)
+
+
+def sched_two_tier_latencies(arrival, size, tau: int, batch: int, c, k: int, g):
+    arrival, size, c, g = _host_f64(arrival), _host_i64(size), _host_f64(c), _host_f64(g)
+    assert c.size > batch
+    lat = np.empty_like(arrival)
+    _check(lib().rec_sched_two_tier_latencies(arrival.ctypes.data, size.ctypes.data, arrival.size, tau, batch, c.ctypes.data,
+                                              k, g.ctypes.data, g.size - 1, lat.ctypes.data), "rec_sched_two_tier_latencies")
+    return lat
+
+
+def sched_two_tier_max_qps(unit_arrival, size, tau: int, batch: int, c, k: int, g, p: float, sla: float,
+                           iters: int = 40) -> float:
+    unit_arrival, size, c, g = _host_f64(unit_arrival), _host_i64(size), _host_f64(c), _host_f64(g)
+    assert c.size > batch
+    return lib().rec_sched_two_tier_max_qps(unit_arrival.ctypes.data, size.ctypes.data, size.size, tau, batch,
+                                            c.ctypes.data, k, g.ctypes.data, g.size - 1, p, sla, iters)
 
 
 class _Request(C.Structure):

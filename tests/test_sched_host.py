@@ -74,3 +74,30 @@ def test_max_qps_and_hill_climb_match_oracle(rec):
     for q in ([1.0], [1.0, 2.0, 3.0], [1.0, 2.0, 2.0, 5.0], [3.0, 1.0, 9.0], [1.0, 2.0, 1.5, 4.0]):
         assert rec.sched_hill_climb(q) == oracle.hill_climb(np.array(q))
     assert rec.sched_hill_climb([]) == -1
+
+
+def test_two_tier_matches_oracle(rec):
+    r = np.random.default_rng(8)
+    n, B = 600, 16
+    c = np.concatenate([[0.0], 2e-3 + 1e-4 * np.arange(1, B + 1)])
+    g = np.concatenate([[0.0], 3e-4 + 2e-7 * np.arange(1, 1001)])
+    sizes = synth.lognormal_query_sizes(synth.MASTER_SEED, n)
+    unit = synth.unit_poisson_arrivals(synth.MASTER_SEED, n)
+    for tau in (1, 2, 17, 100, 400, 1001):
+        for k in (1, 3, 16):
+            for rate in (20.0, 300.0, 5000.0):
+                a = unit / rate
+                assert np.array_equal(rec.sched_two_tier_latencies(a, sizes, tau, B, c, k, g),
+                                      oracle.two_tier_latencies(a, sizes, tau, B, c, k, g)), (tau, k, rate)
+    qps_p, qps_o = [], []
+    for tau in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1001):
+        qps_p.append(rec.sched_two_tier_max_qps(unit, sizes, tau, B, c, 16, g, 0.95, 0.05))
+        qps_o.append(oracle.two_tier_max_qps(unit, sizes, tau, B, c, 16, g, 0.95, 0.05))
+    assert qps_p == qps_o
+    assert rec.sched_hill_climb(qps_p) == oracle.hill_climb(np.array(qps_o))
+    assert rec.sched_two_tier_max_qps(unit, sizes, 1001, B, c, 16, g, 0.95, 1e-4) == 0.0        # idle system misses it
+    # argument errors
+    assert math.isnan(rec.sched_two_tier_max_qps(unit, sizes, 4, B, c, 0, g, 0.95, 0.05))        # no workers
+    assert math.isnan(rec.sched_two_tier_max_qps(unit, sizes, 4, B, c, 2, g[:500], 0.95, 0.05))  # a size beyond g
+    with pytest.raises(rec.RecError):
+        rec.sched_two_tier_latencies([1.0, 0.5], [3, 3], 4, B, c, 2, g)
