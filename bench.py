@@ -503,6 +503,10 @@ def batch_size_tuning(cfg, model, gen, torch, rec, synth, workload, np,
     if pool_streams is not None:
         res["live_hill_climb"] = {f"{t}ms": live_hill_climb(cfg, model, gen, sizes, unit, t * 1e-3, cands, pool_streams,
                                                             rec, workload, np) for t in (1.0, 5.0)}
+        # the same with the requests of a query dealt over the streams (request-level parallelism)
+        res["live_hill_climb_spread_requests"] = {
+            f"{t}ms": live_hill_climb(cfg, model, gen, sizes, unit, t * 1e-3, cands, pool_streams, rec, workload, np,
+                                      spread=True) for t in (0.25, 1.0)}
     return res
 
 
@@ -593,7 +597,7 @@ def offload_threshold_tuning(cfg, gpu_table, gen, torch, rec, synth, workload, n
     return res
 
 
-def live_hill_climb(cfg, model, gen, sizes, unit, sla_s, cands, pool_streams, rec, workload, np, n=400):
+def live_hill_climb(cfg, model, gen, sizes, unit, sla_s, cands, pool_streams, rec, workload, np, n=400, spread=False):
     """Section IV-C on live measurements: for batch sizes 1, 2, 4, ... measure the largest Poisson
     rate the device sustains with p95 <= target (first `n` queries of the trace, requests spread
     over the stream pool) and climb until that rate degrades."""
@@ -602,7 +606,7 @@ def live_hill_climb(cfg, model, gen, sizes, unit, sla_s, cands, pool_streams, re
     for Bs in cands:
         staged = [[workload.DeviceBatch(workload.slice_batch(src[q % len(src)], cfg.T, s, c))
                    for s, c in rec.split_query(int(m), Bs)] for q, m in enumerate(sizes[:n].tolist())]
-        tr = rec.ServeTrace(model, staged, pool_streams)
+        tr = rec.ServeTrace(model, staged, pool_streams, spread_requests=spread)
         tr.run(np.zeros(n))                                               # warm
         idle = tr.run(np.arange(n) * 2.0 * sla_s)                         # no queueing: service times alone
         if rec.sched_percentile(idle, 0.95) > sla_s:
@@ -611,7 +615,8 @@ def live_hill_climb(cfg, model, gen, sizes, unit, sla_s, cands, pool_streams, re
             start = max(qps[-1] if qps else 0.0, 0.5 / sla_s)
             qps.append(live_max_qps(tr, unit[:n], sla_s, start, rec, bracket_steps=14, bisect_steps=4))
         del tr, staged
-        print(f"[sched] live climb, target {sla_s * 1e3:g} ms, batch {Bs}: {qps[-1]:.0f} queries/s", file=sys.stderr, flush=True)
+        print(f"[sched] live climb{' (requests spread)' if spread else ''}, target {sla_s * 1e3:g} ms, batch {Bs}: "
+              f"{qps[-1]:.0f} queries/s", file=sys.stderr, flush=True)
         if len(qps) > 1 and qps[-1] < qps[-2]:
             break                                                          # degraded: the climb stops here
     k = rec.sched_hill_climb(qps)

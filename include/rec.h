@@ -301,14 +301,17 @@ rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, cons
                            const double* arrival_s, int64_t n_queries, float* prob, void* workspace,
                            size_t workspace_bytes, void* stream, double* latency_s);
 
-/* rec_serve_trace over several streams: query q runs on streams[q % n_streams] with
- * prob[q % n_streams] (DEV fp32 [max request B] each) and workspaces[q % n_streams]; a query's
- * requests stay in order on its stream, queries on different streams overlap on the device.
- * Everything else as rec_serve_trace (which is this call with one stream). */
+/* rec_serve_trace over several streams, each with its own prob[k] (DEV fp32 [max request B]) and
+ * workspaces[k].  spread_requests = 0: query q runs on streams[q % n_streams], its requests in
+ * order on that stream; queries on different streams overlap on the device.  spread_requests != 0:
+ * the requests themselves are dealt round-robin over the streams, so the requests of one query run
+ * side by side -- the request-level parallelism of Section IV-A with streams in the place of
+ * cores -- and the query is complete when the last of them is.  Everything else as
+ * rec_serve_trace (which is this call with one stream). */
 rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests, const int64_t* query_first,
                                 const double* arrival_s, int64_t n_queries, float* const* prob,
                                 void* const* workspaces, size_t workspace_bytes, void* const* streams,
-                                int32_t n_streams, double* latency_s);
+                                int32_t n_streams, int32_t spread_requests, double* latency_s);
 
 #ifdef __cplusplus
 }

@@ -326,27 +326,37 @@ rec_status rec_serve_trace(const rec_model* m, const rec_request* requests, cons
                            const double* arrival_s, int64_t n_queries, float* prob, void* workspace,
                            size_t workspace_bytes, void* stream, double* latency_s) {
     return rec_serve_trace_many(m, requests, query_first, arrival_s, n_queries, &prob, &workspace, workspace_bytes, &stream,
-                                1, latency_s);
+                                1, 0, latency_s);
 }
 
 rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests, const int64_t* query_first,
                                 const double* arrival_s, int64_t n_queries, float* const* prob,
                                 void* const* workspaces, size_t workspace_bytes, void* const* streams,
-                                int32_t n_streams, double* latency_s) {
+                                int32_t n_streams, int32_t spread_requests, double* latency_s) {
     if (n_queries < 0 || n_streams < 1) return REC_ERR_BAD_SHAPE;
     if (n_queries == 0) return REC_OK;
     if (!m || !requests || !query_first || !arrival_s || !latency_s || !prob || !workspaces || !streams) return REC_ERR_NULL;
     for (int32_t k = 0; k < n_streams; ++k)
         if (!prob[k]) return REC_ERR_NULL;
+    int64_t n_marks = 0;
     for (int64_t q = 0; q < n_queries; ++q) {
-        if (query_first[q + 1] < query_first[q] || arrival_s[q] < 0.0) return REC_ERR_BAD_SHAPE;
+        const int64_t n_req = query_first[q + 1] - query_first[q];
+        if (n_req < 0 || arrival_s[q] < 0.0) return REC_ERR_BAD_SHAPE;
         if (q > 0 && arrival_s[q] < arrival_s[q - 1]) return REC_ERR_BAD_SHAPE;
+        n_marks += spread_requests ? std::max<int64_t>(1, std::min<int64_t>(n_req, n_streams)) : 1;
     }
-    // done[q] marks the completion of query q; origin[k] is time zero as stream k sees it
-    std::vector<hipEvent_t> done((size_t)n_queries, nullptr), origin((size_t)n_streams, nullptr);
+    // A query is complete when the last of its requests on every stream it used is: one event per
+    // (query, stream used), recorded behind that request.  origin[k] is time zero as stream k sees it.
+    struct Mark {
+        int32_t stream;
+        hipEvent_t event;
+    };
+    std::vector<Mark> marks((size_t)n_marks, Mark{0, nullptr});
+    std::vector<int64_t> mark_first((size_t)n_queries + 1, 0);
+    std::vector<hipEvent_t> origin((size_t)n_streams, nullptr);
     auto cleanup = [&]() {
-        for (hipEvent_t e : done)
-            if (e) (void)hipEventDestroy(e);
+        for (Mark& k : marks)
+            if (k.event) (void)hipEventDestroy(k.event);
         for (hipEvent_t e : origin)
             if (e) (void)hipEventDestroy(e);
     };
@@ -355,8 +365,8 @@ rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests,
         for (int32_t k = 0; k < n_streams; ++k) ok = (hipStreamSynchronize(static_cast<hipStream_t>(streams[k])) == hipSuccess) && ok;
         return ok;
     };
-    for (auto& e : done)
-        if (hipEventCreate(&e) != hipSuccess) {
+    for (Mark& k : marks)
+        if (hipEventCreate(&k.event) != hipSuccess) {
             cleanup();
             return REC_ERR_DEVICE;
         }
@@ -378,27 +388,45 @@ rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests,
     }
     const auto t0 = std::chrono::steady_clock::now();
     rec_status st = REC_OK;
+    int64_t next_mark = 0;
+    int64_t turn = 0;                                     // round-robin position over the streams
+    std::vector<char> used((size_t)n_streams, 0);
     for (int64_t q = 0; q < n_queries && st == REC_OK; ++q) {
-        const int32_t k = (int32_t)(q % n_streams);
+        mark_first[(size_t)q] = next_mark;
         while (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < arrival_s[q]) {
         }
+        std::fill(used.begin(), used.end(), 0);
+        const int32_t home = (int32_t)(turn % n_streams);
         for (int64_t r = query_first[q]; r < query_first[q + 1] && st == REC_OK; ++r) {
+            const int32_t k = spread_requests ? (int32_t)(turn++ % n_streams) : home;
             const rec_request& rq = requests[r];
             st = rec_model_forward(m, rq.dense, rq.indices, rq.n_indices, rq.lengths, rq.B, prob[k], workspaces[k],
                                    workspace_bytes, streams[k]);
+            used[(size_t)k] = 1;
         }
-        if (st == REC_OK && hipEventRecord(done[(size_t)q], static_cast<hipStream_t>(streams[k])) != hipSuccess)
-            st = REC_ERR_DEVICE;
+        if (!spread_requests) ++turn;
+        if (query_first[q + 1] == query_first[q]) used[(size_t)home] = 1;      // an empty query still gets a time stamp
+        for (int32_t k = 0; k < n_streams && st == REC_OK; ++k) {
+            if (!used[(size_t)k]) continue;
+            Mark& mk = marks[(size_t)next_mark++];
+            mk.stream = k;
+            if (hipEventRecord(mk.event, static_cast<hipStream_t>(streams[k])) != hipSuccess) st = REC_ERR_DEVICE;
+        }
     }
+    mark_first[(size_t)n_queries] = next_mark;
     if (!sync_all() && st == REC_OK) st = REC_ERR_DEVICE;
     if (st == REC_OK) {
-        for (int64_t q = 0; q < n_queries; ++q) {
-            float ms = 0.f;
-            if (hipEventElapsedTime(&ms, origin[(size_t)(q % n_streams)], done[(size_t)q]) != hipSuccess) {
-                st = REC_ERR_DEVICE;
-                break;
+        for (int64_t q = 0; q < n_queries && st == REC_OK; ++q) {
+            double finished = 0.0;
+            for (int64_t i = mark_first[(size_t)q]; i < mark_first[(size_t)q + 1]; ++i) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, origin[(size_t)marks[(size_t)i].stream], marks[(size_t)i].event) != hipSuccess) {
+                    st = REC_ERR_DEVICE;
+                    break;
+                }
+                finished = std::max(finished, (double)ms * 1e-3);
             }
-            latency_s[q] = (double)ms * 1e-3 - arrival_s[q];
+            latency_s[q] = finished - arrival_s[q];
         }
     }
     cleanup();

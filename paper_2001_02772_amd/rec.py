@@ -127,7 +127,7 @@ def lib():
     L.rec_model_forward_many.restype = C.c_int
     L.rec_model_forward_many.argtypes = [vp, vp, vp, i64, vp, vp, sz, i32]
     L.rec_serve_trace_many.restype = C.c_int
-    L.rec_serve_trace_many.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, i32, vp]
+    L.rec_serve_trace_many.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, i32, i32, vp]
     L.rec_serve_trace.restype = C.c_int
     L.rec_serve_trace.argtypes = [vp, vp, vp, vp, i64, vp, vp, sz, vp, vp]
     _lib = L
@@ -451,8 +451,8 @@ class ServeTrace:
     device batches); run(arrival_s) replays the trace and returns per-query latencies in seconds.
     streams: objects with .cuda_stream (None: torch's current stream)."""
 
-    def __init__(self, model: "Model", queries, streams=None):
-        self.model, self.keep = model, queries
+    def __init__(self, model: "Model", queries, streams=None, spread_requests: bool = False):
+        self.model, self.keep, self.spread = model, queries, int(spread_requests)
         flat = [r for q in queries for r in q]
         self.n = len(queries)
         self.reqs = (_Request * max(len(flat), 1))()
@@ -474,7 +474,8 @@ class ServeTrace:
         lat = np.empty(self.n, dtype=np.float64)
         st = lib().rec_serve_trace_many(self.model._h, C.addressof(self.reqs), self.first.ctypes.data,
                                         arrival_s.ctypes.data, self.n, C.addressof(self.probp), C.addressof(self.wsp),
-                                        self.ws_bytes, C.addressof(self.streams), len(self.streams), lat.ctypes.data)
+                                        self.ws_bytes, C.addressof(self.streams), len(self.streams), self.spread,
+                                        lat.ctypes.data)
         _check(st, "rec_serve_trace_many")
         return lat
 

@@ -69,7 +69,7 @@ def test_serving_entry_points_reject_bad_arguments_on_the_host(rec):
     assert L.rec_model_forward_many(None, None, None, 0, None, None, 0, 1) == rec.OK         # nothing to do
     assert L.rec_model_forward_many(None, None, None, 3, None, None, 0, 0) == rec.ERR_BAD_SHAPE
     assert L.rec_model_forward_many(None, None, None, 3, None, None, 0, 2) == rec.ERR_NULL
-    assert L.rec_serve_trace_many(None, None, None, None, 0, None, None, 0, None, 1, None) == rec.OK
-    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 0, None) == rec.ERR_BAD_SHAPE
-    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 1, None) == rec.ERR_NULL
+    assert L.rec_serve_trace_many(None, None, None, None, 0, None, None, 0, None, 1, 0, None) == rec.OK
+    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 0, 1, None) == rec.ERR_BAD_SHAPE
+    assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 1, 1, None) == rec.ERR_NULL
     assert L.rec_serve_trace(None, None, None, None, -1, None, None, 0, None, None) == rec.ERR_BAD_SHAPE

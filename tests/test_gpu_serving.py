@@ -146,6 +146,12 @@ def test_replay_over_stream_pool(setup):
     gap = 5e-3
     lat2 = tr.run(np.arange(len(sizes)) * gap)
     assert np.all(lat2 > 0) and np.all(lat2 < gap)
+    # requests dealt over the streams: a query is complete when the slowest of its requests is
+    spread = rec.ServeTrace(model, queries, pool.streams, spread_requests=True)
+    lat3 = spread.run(np.zeros(len(sizes)))
+    assert np.all(lat3 > 0) and lat3.max() < 1.0
+    lat4 = spread.run(np.arange(len(sizes)) * gap)
+    assert np.all(lat4 > 0) and np.all(lat4 < gap)
     # each stream's output buffer holds the last request of the last query that ran on it
     for k in range(3):
         q = max(i for i in range(len(sizes)) if i % 3 == k)
