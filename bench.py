@@ -23,7 +23,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X fp32 matrix, published
 # HBM bytes per launch of the pooling kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled
 # by a copy-shaped reference dispatch (see profiles/sls_kernel_rmc2_counters.md).  Valid for the
 # sls_kernel these were taken with; set an entry to None when that kernel changes.
-SLS_COUNTED_TRAFFIC_BYTES = {"rmc2": 316.4e6, "rmc2-uniform": 705.9e6}
+SLS_COUNTED_TRAFFIC_BYTES = {"rmc2": 368.5e6, "rmc2-uniform": 824.2e6}
 
 
 def parse():
@@ -299,24 +299,26 @@ def main():
 
     if a.copy_calibration:
         # Reference dispatches of known size for scaling FETCH_SIZE / WRITE_SIZE:
-        # (1) the pooling kernel itself as a plain copy -- one table, bag i = [row i], so it reads
-        #     n rows (+ n indices, n+1 offsets) and writes n rows with the request pattern of the real run;
+        # (1) the pooling kernel itself streaming a table once -- one table, bag i = rows 4i..4i+3
+        #     (four lookups per bag keep it on sls_kernel, not on the short-bag kernel), so it reads n
+        #     rows (+ n indices, n/4+1 offsets) and writes n/4 rows with the request pattern of the real run;
         # (2) the runtime's device-to-device copy of 256 MiB.
-        n = min(cfg.R, 500_000)
+        n = min(cfg.R, 500_000) // 4 * 4
+        nb = n // 4
         one = rec.Tables([model.tables.tensors[0]])
         idx = torch.arange(n, dtype=torch.int32, device="cuda")
-        off = torch.arange(n + 1, dtype=torch.int64, device="cuda")
-        dst_rows = torch.empty((n, 1, cfg.D), dtype=torch.float32, device="cuda")
+        off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * 4
+        dst_rows = torch.empty((nb, 1, cfg.D), dtype=torch.float32, device="cuda")
         for _ in range(3):
-            rec.sls_forward_offsets(one, idx, off, n, out=dst_rows, out_stride_b=cfg.D, out_stride_t=cfg.D)
+            rec.sls_forward_offsets(one, idx, off, nb, out=dst_rows, out_stride_b=cfg.D, out_stride_t=cfg.D)
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-        out["copy_calibration"] = {"sls_as_copy": {"grid_threads": ((n + 3) // 4) * 256,
-                                                   "read_bytes": n * (4 * cfg.D + 4) + 8 * (n + 1),
-                                                   "write_bytes": n * 4 * cfg.D},
+        out["copy_calibration"] = {"sls_as_copy": {"grid_threads": ((nb + 3) // 4) * 256,
+                                                   "read_bytes": n * (4 * cfg.D + 4) + 8 * (nb + 1),
+                                                   "write_bytes": nb * 4 * cfg.D},
                                    "memcpy_d2d_bytes": int(src.numel())}
 
     if a.sweep:
