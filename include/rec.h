@@ -11,11 +11,15 @@
  *
  * Conventions
  *   - Pointers marked DEV are device pointers owned by the caller; pointers
- *     marked HOST are host pointers read before the call returns.  The library
- *     never allocates or frees device memory; scratch comes in through the
+ *     marked HOST are host pointers read before the call returns.  The compute
+ *     calls never allocate or free device memory; scratch comes in through the
  *     `workspace` arguments (256-byte aligned, at least *_workspace_bytes()).
+ *     The only calls that create device-side resources are rec_model_create
+ *     (at most one buffer, see there) and rec_stream_pool_create (streams).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Every call except rec_sls_validate only enqueues work and returns.
+ *     The compute calls only enqueue work and return; the synchronous ones say
+ *     so: rec_sls_validate, rec_model_create, rec_stream_pool_synchronize /
+ *     _destroy, rec_serve_trace and rec_serve_trace_many.
  *   - Errors that the host can see (null pointer, bad shape, small workspace)
  *     are returned before anything is launched.  Errors that depend on device
  *     data (negative length, lengths not summing to n_indices, index out of
