@@ -70,9 +70,9 @@ def time_steps(fn, steps, warmup, torch):
 def time_many(model, rec, reqs, probs, streams, steps, warmup, torch):
     """K forward passes enqueued by one library call, request i on stream i % S; seconds per step."""
     pick = lambda n: ([reqs[i % len(reqs)] for i in range(n)], [probs[i % len(probs)] for i in range(n)])
-    warm = rec.ForwardMany(model, *pick(max(warmup, 1)), streams)
-    timed = rec.ForwardMany(model, *pick(steps), streams, workspaces=warm.ws)
-    warm.launch()
+    timed = rec.ForwardMany(model, *pick(steps), streams)
+    if warmup > 0:
+        rec.ForwardMany(model, *pick(warmup), streams, workspaces=timed.ws).launch()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     timed.launch()
