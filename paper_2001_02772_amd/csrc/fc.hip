@@ -365,7 +365,7 @@ rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const
 rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, const int32_t* widths, int32_t n_layers,
                                 rec_dtype wdtype, rec_act hidden_act, rec_act final_act, const float* x, int64_t ldx,
                                 float* y, int64_t ldy, int32_t B, void* workspace, size_t workspace_bytes, void* stream,
-                                const rec_scan_job* scan) {
+                                const rec_scan_job* scan, const rec_interact_job* inter) {
     if (!W || !bias || !widths) return REC_ERR_NULL;
     if (n_layers < 1 || B < 0) return REC_ERR_BAD_SHAPE;
     if (wdtype != REC_F32 && wdtype != REC_BF16) return REC_ERR_UNSUPPORTED;
@@ -412,6 +412,17 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
             scan = nullptr;
         }
     }
+    if (inter) {
+        // the interaction is computed by the first launch when that is a fused run that can take it,
+        // else by its own kernel into the stack's input buffer
+        if (inter->out != x || inter->ldo != ldx) return REC_ERR_BAD_SHAPE;
+        if (!(narrow_run(0) > 0 && rec_fused_interact_ok(inter->V, inter->D))) {
+            const rec_status st = rec_interact_padded(inter->vecs, B, inter->V, inter->D, inter->out, inter->ldo, inter->zero_to,
+                                                      stream);
+            if (st != REC_OK) return st;
+            inter = nullptr;
+        }
+    }
     while (l < n_layers) {
         const int32_t run = narrow_run(l);
         const int32_t l_end = run > 0 ? l + run : l + 1;
@@ -437,6 +448,9 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
             a.y_bf16 = bf && !last;
             a.ldy = ldd;
             a.B = B;
+            a.vecs = (l == 0 && inter) ? inter->vecs : nullptr;
+            a.V = inter ? inter->V : 0;
+            a.D = inter ? inter->D : 0;
             st = rec_fused_mlp_launch(a, wdtype, scan, s);
             scan = nullptr;
         } else {

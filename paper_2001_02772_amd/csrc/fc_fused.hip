@@ -22,6 +22,12 @@ constexpr int FM_ROWS = 16;
 constexpr int FM_WAVES = 16;
 constexpr int FM_THREADS = FM_WAVES * 64;
 
+// Interaction computed in the block (see rec_fused_mlp_args::vecs): a sample's V vectors are kept
+// in LDS with a row stride of D + 1 floats (odd, so the rows of different vectors fall into
+// different banks), at most FI_SAMPLE floats per sample and FI_PAIRS pairs.
+constexpr int FI_SAMPLE = 1024;
+constexpr int FI_PAIRS = 1024;
+
 template <bool BF16>
 struct FM {
     static constexpr int MAXW = BF16 ? REC_FUSED_MAX_WIDTH_BF16 : REC_FUSED_MAX_WIDTH_F32;
@@ -247,7 +253,7 @@ __device__ __forceinline__ void tile_out(const floatx4& acc, int n, int N, int q
 // the current one; the only exposed latencies are the first load and the input rows.  What bounds
 // a block is the bytes it keeps in flight, so all 16 waves are given weight rows to fetch.
 // (Three items ahead instead of one measured slower: 15.7 -> 18.9 us for 512-128-1 in fp32.)
-template <bool BF16>
+template <bool BF16, bool INTER>
 __device__ __forceinline__ void fused_mlp_block(const rec_fused_mlp_args& a, const int block) {
     typedef FM<BF16> C;
     typedef typename C::act_t act_t;
@@ -271,7 +277,57 @@ __device__ __forceinline__ void fused_mlp_block(const rec_fused_mlp_args& a, con
     // stage the 16 input rows, zero-padded to a whole number of k-chunks.  The loads of a round
     // are independent and issued together (wide ones when the rows allow), so the whole tile
     // costs about one memory latency.
-    {
+    if constexpr (INTER) {
+        // Pairwise-dot interaction of the block's 16 samples, straight into the first layer's input
+        // buffer (Section II-A, "Feature Interaction"): every thread takes (sample, output column)
+        // pairs; a column is either a copy of the dense vector or one dot product of D terms.
+        __shared__ float vs[FM_ROWS * FI_SAMPLE];
+        __shared__ unsigned char pair_i[FI_PAIRS], pair_j[FI_PAIRS];
+        act_t* buf = reinterpret_cast<act_t*>(lds);
+        const int V = a.V, D = a.D, ldv = D + 1, P = V * (V - 1) / 2, width = D + P;
+        const int K0p = (t.w0 + KCH - 1) / KCH * KCH;
+        const int per_sample = V * D;
+        const float* __restrict__ src = a.vecs + (int64_t)m0 * per_sample;
+        const int rows = (a.B - m0 < FM_ROWS) ? a.B - m0 : FM_ROWS;
+        for (int e0 = 0; e0 < FM_ROWS * per_sample; e0 += 4 * FM_THREADS) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + i * FM_THREADS + tid;
+                const bool ok = e < rows * per_sample;
+                v[i] = src[ok ? e : 0];
+                if (!ok) v[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + i * FM_THREADS + tid;
+                if (e < FM_ROWS * per_sample) {
+                    const int s = e / per_sample, r = e - s * per_sample;
+                    vs[s * FI_SAMPLE + (r / D) * ldv + r % D] = v[i];
+                }
+            }
+        }
+        for (int p = tid; p < P; p += FM_THREADS) {
+            int i = 1;
+            while ((i + 1) * i / 2 <= p) ++i;
+            pair_i[p] = (unsigned char)i;
+            pair_j[p] = (unsigned char)(p - i * (i - 1) / 2);
+        }
+        __syncthreads();
+        for (int c = tid; c < FM_ROWS * K0p; c += FM_THREADS) {
+            const int s = c / K0p, col = c - s * K0p;
+            const float* __restrict__ sv = vs + s * FI_SAMPLE;
+            float val = 0.f;
+            if (col < D) {
+                val = sv[col];
+            } else if (col < width) {
+                const float* __restrict__ vi = sv + pair_i[col - D] * ldv;
+                const float* __restrict__ vj = sv + pair_j[col - D] * ldv;
+                for (int d = 0; d < D; ++d) val = fmaf(vi[d], vj[d], val);
+            }
+            buf[s * C::LDA + col] = to_act<BF16>(val);
+        }
+    } else {
         act_t* buf = reinterpret_cast<act_t*>(lds);
         const int K0 = t.w0;
         const int K0p = (K0 + KCH - 1) / KCH * KCH;
@@ -401,9 +457,9 @@ __device__ __forceinline__ void fused_mlp_block(const rec_fused_mlp_args& a, con
     }
 }
 
-template <bool BF16>
+template <bool BF16, bool INTER>
 __global__ __launch_bounds__(FM_THREADS) void fused_mlp_kernel(rec_fused_mlp_args a) {
-    fused_mlp_block<BF16>(a, (int)blockIdx.x);
+    fused_mlp_block<BF16, INTER>(a, (int)blockIdx.x);
 }
 
 // The same stack with the bag-offsets scan in the first `scan_tiles` blocks of the launch: the
@@ -416,14 +472,26 @@ __global__ __launch_bounds__(FM_THREADS) void fused_mlp_scan_kernel(rec_fused_ml
                                                                     int64_t n, int64_t* __restrict__ off, int vec_ok,
                                                                     int scan_tiles) {
     if ((int)blockIdx.x < scan_tiles) offsets_block(len, n, off, vec_ok, (int)blockIdx.x, true);
-    else fused_mlp_block<BF16>(a, (int)blockIdx.x - scan_tiles);
+    else fused_mlp_block<BF16, false>(a, (int)blockIdx.x - scan_tiles);
 }
 
 }  // namespace
 
+bool rec_fused_interact_ok(int32_t V, int32_t D) {
+    // LDS space per sample, the pair table (indices fit a byte), and the time the dots take at 16 samples a block
+    return V >= 1 && V <= 255 && D >= 1 && (int64_t)V * (D + 1) <= FI_SAMPLE && (int64_t)V * (V - 1) / 2 <= FI_PAIRS &&
+           (int64_t)V * V * D <= 8192;
+}
+
 rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const rec_scan_job* scan, hipStream_t s) {
     const unsigned blocks = (unsigned)((a.B + FM_ROWS - 1) / FM_ROWS);
-    if (scan) {
+    if (a.vecs) {
+        if (scan || !rec_fused_interact_ok(a.V, a.D) || a.width[0] < a.D + a.V * (a.V - 1) / 2) return REC_ERR_BAD_SHAPE;
+        if (dt == REC_BF16)
+            hipLaunchKernelGGL((fused_mlp_kernel<true, true>), dim3(blocks), dim3(FM_THREADS), 0, s, a);
+        else
+            hipLaunchKernelGGL((fused_mlp_kernel<false, true>), dim3(blocks), dim3(FM_THREADS), 0, s, a);
+    } else if (scan) {
         const int tiles = rec_scan_parallel_tiles(scan->n);
         if (tiles < 1 || !scan->lengths || !scan->offsets) return REC_ERR_BAD_SHAPE;
         const int vec_ok = (int)rec_aligned(scan->lengths, 16);
@@ -434,9 +502,9 @@ rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const
             hipLaunchKernelGGL(fused_mlp_scan_kernel<false>, dim3(blocks + tiles), dim3(FM_THREADS), 0, s, a, scan->lengths,
                                scan->n, scan->offsets, vec_ok, tiles);
     } else if (dt == REC_BF16) {
-        hipLaunchKernelGGL(fused_mlp_kernel<true>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
+        hipLaunchKernelGGL((fused_mlp_kernel<true, false>), dim3(blocks), dim3(FM_THREADS), 0, s, a);
     } else {
-        hipLaunchKernelGGL(fused_mlp_kernel<false>, dim3(blocks), dim3(FM_THREADS), 0, s, a);
+        hipLaunchKernelGGL((fused_mlp_kernel<false, false>), dim3(blocks), dim3(FM_THREADS), 0, s, a);
     }
     REC_CHECK_LAUNCH();
     return REC_OK;

@@ -245,10 +245,11 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
     st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.vecs + D,
                               (int64_t)V * D, D, w.sls, w.sls_bytes, stream, REC_SLS_POOL_ONLY);
     if (st != REC_OK) return st;
-    st = rec_interact_padded(w.vecs, B, V, D, w.inter, m->ld_inter, m->top_k0, stream);
-    if (st != REC_OK) return st;
-    return rec_mlp_forward(m->top_W.data(), m->top_b.data(), m->top_widths_run.data(), (int32_t)m->top_W.size(), m->dt,
-                           REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, m->ld_inter, prob, 1, B, w.mlp, w.mlp_bytes, stream);
+    // the interaction runs inside the predictor stack's first launch when it can, else on its own
+    const rec_interact_job inter = {w.vecs, V, D, w.inter, m->ld_inter, m->top_k0};
+    return rec_mlp_forward_scan(m->top_W.data(), m->top_b.data(), m->top_widths_run.data(), (int32_t)m->top_W.size(), m->dt,
+                                REC_ACT_RELU, REC_ACT_SIGMOID, w.inter, m->ld_inter, prob, 1, B, w.mlp, w.mlp_bytes, stream,
+                                nullptr, &inter);
 }
 
 }  // extern "C"

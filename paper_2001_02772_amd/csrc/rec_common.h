@@ -54,7 +54,13 @@ struct rec_fused_mlp_args {
     int32_t y_bf16;
     int64_t ldy;
     int32_t B;
+    // When vecs is not NULL the input rows are not read from x: row b is the pairwise-dot
+    // interaction of vecs[b] ([V][D] fp32, samples V*D floats apart) -- slot 0, then the strict lower
+    // triangle of V V^T row by row -- computed by the block, zero-filled up to width[0].
+    const float* vecs;
+    int32_t V, D;
 };
+bool rec_fused_interact_ok(int32_t V, int32_t D);               // the fused kernel can take this interaction
 
 // An offsets scan (lengths -> bag starts) that may ride along with another launch: the scan of
 // a batch is a few blocks of latency-bound work, so it shares a launch with the dense stack's
@@ -67,6 +73,17 @@ struct rec_scan_job {
 int rec_scan_parallel_tiles(int64_t n);                          // > 0: independent tiles; 0: serial scan only
 rec_status rec_scan_launch(const rec_scan_job& job, hipStream_t s);
 
+// The interaction in front of a predictor stack: done inside the stack's first launch when that
+// launch is a fused run and the shape allows, else by a launch of its own into out (row stride ldo,
+// zero-filled up to zero_to), which must be the stack's x.
+struct rec_interact_job {
+    const float* vecs;      // [B][V][D]
+    int32_t V, D;
+    float* out;
+    int64_t ldo;
+    int32_t zero_to;
+};
+
 // `scan` (may be NULL): also run this scan in the same launch; it must have parallel tiles.
 rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const rec_scan_job* scan, hipStream_t s);
 
@@ -75,7 +92,7 @@ rec_status rec_fused_mlp_launch(const rec_fused_mlp_args& a, rec_dtype dt, const
 rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, const int32_t* widths, int32_t n_layers,
                                 rec_dtype wdtype, rec_act hidden_act, rec_act final_act, const float* x, int64_t ldx,
                                 float* y, int64_t ldy, int32_t B, void* workspace, size_t workspace_bytes, void* stream,
-                                const rec_scan_job* scan);
+                                const rec_scan_job* scan, const rec_interact_job* inter = nullptr);
 
 // rec_sls_forward in steps: all of it, only the argument checks, or only the pooling launch
 // (the caller has enqueued the scan into rec_sls_workspace_offsets() on the same stream).
