@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "rec_common.h"
+#include "scan_body.h"
 
 struct rec_model {
     int32_t T, D;
@@ -58,11 +59,21 @@ ModelWorkspace carve(const rec_model* m, int32_t B, void* base) {
     return w;
 }
 
-// dst[b][0..F) = src[b][0..F): dense features that skip the dense stack (Section II-A, Wide&Deep)
-__global__ __launch_bounds__(256) void copy_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
-                                                        int32_t B, int32_t F, int64_t ld_dst) {
+// dst[b][0..F) = src[b][0..F): dense features that skip the dense stack (Section II-A, Wide&Deep).
+// The first `scan_tiles` blocks of the launch do the bag-offsets scan instead (see scan_body.h), so
+// a model without a dense stack does not pay a launch for either.
+__global__ __launch_bounds__(SCAN_THREADS) void copy_rows_scan_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                                      int32_t B, int32_t F, int64_t ld_dst,
+                                                                      const int32_t* __restrict__ len, int64_t n_bags,
+                                                                      int64_t* __restrict__ off, int vec_ok, int scan_tiles) {
+    if ((int)blockIdx.x < scan_tiles) {
+        offsets_block(len, n_bags, off, vec_ok, (int)blockIdx.x, true);
+        return;
+    }
     const int64_t n4 = (int64_t)B * (F / 4);
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    const int64_t first = (int64_t)(blockIdx.x - scan_tiles) * SCAN_THREADS + threadIdx.x;
+    const int64_t step = (int64_t)(gridDim.x - scan_tiles) * SCAN_THREADS;
+    for (int64_t i = first; i < n4; i += step) {
         const int64_t b = i / (F / 4);
         const int32_t c = (int32_t)(i - b * (F / 4)) * 4;
         *reinterpret_cast<float4*>(dst + b * ld_dst + c) = *reinterpret_cast<const float4*>(src + b * F + c);
@@ -209,14 +220,24 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
         const int32_t X = m->bottom_widths.back();
         const int64_t ldc = m->ld_inter;
         if (m->bottom_W.empty()) {
-            rec_status st = rec_sls_forward(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X,
-                                            ldc, D, w.sls, w.sls_bytes, stream);
+            rec_status st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B,
+                                                 w.inter + X, ldc, D, w.sls, w.sls_bytes, stream, REC_SLS_CHECK_ONLY);
             if (st != REC_OK) return st;
+            int tiles = rec_scan_parallel_tiles(scan.n);
+            if (tiles < 1) {                                         // very long batch: the scan walks its tiles in one block
+                st = rec_scan_launch(scan, static_cast<hipStream_t>(stream));
+                if (st != REC_OK) return st;
+                tiles = 0;
+            }
             const int64_t n4 = (int64_t)B * (X / 4);
-            const unsigned blocks = (unsigned)std::min<int64_t>((n4 + 255) / 256, 4096);
-            hipLaunchKernelGGL(copy_rows_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), dense, w.inter,
-                               B, X, ldc);
+            const unsigned blocks = (unsigned)std::min<int64_t>((n4 + SCAN_THREADS - 1) / SCAN_THREADS, 1024);
+            hipLaunchKernelGGL(copy_rows_scan_kernel, dim3(blocks + tiles), dim3(SCAN_THREADS), 0,
+                               static_cast<hipStream_t>(stream), dense, w.inter, B, X, ldc, scan.lengths, scan.n, scan.offsets,
+                               (int)rec_aligned(scan.lengths, 16), tiles);
             REC_CHECK_LAUNCH();
+            st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B, w.inter + X, ldc,
+                                      D, w.sls, w.sls_bytes, stream, REC_SLS_POOL_ONLY);
+            if (st != REC_OK) return st;
         } else {
             // the offsets scan rides with the dense stack's first launch; the pooling follows both
             rec_status st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B,
