@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 int rec_gemm_bf16_split(int M, int N, int K) {
     if (K % GB_BK != 0 || K < 256) return 0;
     const int64_t tiles = (int64_t)((M + GB_BM - 1) / GB_BM) * ((N + GB_BN - 1) / GB_BN);
-    if (tiles < 32) return 0;                 // smaller layers do better on the 64x64 / 32x32 kernels
+    if (tiles < 64) return 0;                 // smaller layers do better on the 64x64 / 32x32 kernels
     int S = 1;
     while (S < 8 && tiles * S < 256 && K % (S * 2 * GB_BK) == 0 && K / (S * 2) >= 256) S *= 2;
     return S;
