@@ -309,23 +309,29 @@ void choose_shape(int M, int N, int K, bool bf16, int* shape, int* ksplit) {
     *ksplit = ks;
 }
 
-// Bytes of fp32 partial tiles the stack needs for layers that take the large-tile bf16 kernel.
-size_t splitk_bytes(const int32_t* widths, int32_t n_layers, int32_t B, rec_dtype dt) {
+// Bytes the layers that take the large-tile bf16 kernel need beyond the activation buffers (they run
+// one after another and share the area).  Reserved for the first layer whatever kernel a given batch
+// size ends up on, so the total never shrinks as B grows.
+size_t gemm_area_bytes(const int32_t* widths, int32_t n_layers, int32_t B, rec_dtype dt) {
     size_t mx = 0;
     if (dt != REC_BF16) return 0;
-    for (int32_t l = 0; l < n_layers; ++l) {
-        const size_t b = rec_gemm_bf16_partial_bytes(B, widths[l + 1], widths[l]);
-        mx = b > mx ? b : mx;
-    }
+    if (widths[0] % 64 == 0 && widths[0] >= 256) mx = rec_gemm_bf16_workspace_bytes(B, widths[1], widths[0], false);
+    (void)n_layers;
     return mx;
+}
+
+// The large-tile bf16 kernel takes this layer: big enough, aligned for 16-byte loads.
+bool layer_takes_gemm(const void* x, bool x_bf16, int64_t ldx, const void* W, rec_dtype dt, int32_t B, int32_t n_in,
+                      int32_t n_out) {
+    return dt == REC_BF16 && rec_gemm_bf16_plan(B, n_out, n_in).tiles != 0 && rec_aligned(x, 16) && rec_aligned(W, 16) &&
+           ldx % (x_bf16 ? 8 : 4) == 0 && (!x_bf16 || (int64_t)B * ldx * 2 < ((int64_t)1 << 32));
 }
 
 rec_status launch_layer(const void* x, bool x_bf16, int64_t ldx, const void* W, rec_dtype dt, const float* bias,
                         int32_t B, int32_t n_in, int32_t n_out, int act, void* y, bool y_bf16, int64_t ldy,
-                        float* partial, hipStream_t s) {
-    if (dt == REC_BF16 && rec_gemm_bf16_split(B, n_out, n_in) >= 1 && rec_aligned(x, 16) && rec_aligned(W, 16) &&
-        ldx % (x_bf16 ? 8 : 4) == 0)
-        return rec_gemm_bf16_launch(x, x_bf16, ldx, W, bias, y, y_bf16, ldy, partial, B, n_out, n_in, act, s);
+                        void* gemm_area, const rec_scan_job* scan, hipStream_t s) {
+    if (layer_takes_gemm(x, x_bf16, ldx, W, dt, B, n_in, n_out))
+        return rec_gemm_bf16_launch(x, x_bf16, ldx, W, bias, y, y_bf16, ldy, gemm_area, B, n_out, n_in, act, scan, s);
     int shape, ksplit;
     choose_shape(B, n_out, n_in, dt == REC_BF16, &shape, &ksplit);
     if (dt == REC_F32) {
@@ -349,7 +355,7 @@ size_t rec_mlp_workspace_bytes(const int32_t* widths, int32_t n_layers, int32_t 
     if (!widths || n_layers < 1 || B < 0) return 0;
     for (int32_t l = 0; l <= n_layers; ++l)
         if (widths[l] < 1) return 0;
-    return 2 * hidden_buffer_bytes(widths, n_layers, B, wdtype) + splitk_bytes(widths, n_layers, B, wdtype);
+    return 2 * hidden_buffer_bytes(widths, n_layers, B, wdtype) + gemm_area_bytes(widths, n_layers, B, wdtype);
 }
 
 rec_status rec_mlp_forward(const void* const* W, const float* const* bias, const int32_t* widths,
@@ -379,9 +385,9 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
     if (!x || !y) return REC_ERR_NULL;
     if (ldx < widths[0] || ldy < widths[n_layers]) return REC_ERR_BAD_SHAPE;
     const size_t half = hidden_buffer_bytes(widths, n_layers, B, wdtype);
-    const size_t need = 2 * half + splitk_bytes(widths, n_layers, B, wdtype);
+    const size_t need = 2 * half + gemm_area_bytes(widths, n_layers, B, wdtype);
     if (need > 0 && (!workspace || !rec_aligned(workspace, 256) || workspace_bytes < need)) return REC_ERR_WORKSPACE;
-    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * half);
+    void* gemm_area = static_cast<char*>(workspace) + 2 * half;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf = (wdtype == REC_BF16);
     const void* cur = x;
@@ -398,13 +404,22 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
         return run;
     };
     if (scan) {
-        // the scan rides in the first fused launch of the stack; without one (or when it has no
-        // parallel tiles) it gets a launch of its own up front
+        // the scan rides in the stack's first launch that can carry it -- a fused run of narrow layers,
+        // or the preparing launch of a large-tile layer; without one (or when the scan has no parallel
+        // tiles) it gets a launch of its own up front
         bool can_ride = false;
-        for (int32_t i = 0; i < n_layers && !can_ride;) {
-            const int32_t run = narrow_run(i);
-            can_ride = run > 0;
-            i += run > 0 ? run : 1;
+        {
+            bool in_bf16 = false;
+            int64_t in_ld = ldx;
+            const void* in = x;
+            for (int32_t i = 0; i < n_layers && !can_ride;) {
+                const int32_t run = narrow_run(i);
+                can_ride = run > 0 || layer_takes_gemm(in, in_bf16, in_ld, W[i], wdtype, B, widths[i], widths[i + 1]);
+                i += run > 0 ? run : 1;
+                in = workspace;                       // hidden activations: 256-byte aligned halves of the workspace
+                in_bf16 = bf;
+                in_ld = hidden_ld(widths[i < n_layers ? i : n_layers], wdtype);
+            }
         }
         if (!can_ride || rec_scan_parallel_tiles(scan->n) < 1) {
             const rec_status st = rec_scan_launch(*scan, s);
@@ -454,8 +469,11 @@ rec_status rec_mlp_forward_scan(const void* const* W, const float* const* bias, 
             st = rec_fused_mlp_launch(a, wdtype, scan, s);
             scan = nullptr;
         } else {
+            const bool carries = scan && layer_takes_gemm(cur, cur_bf16, ld, W[l], wdtype, B, widths[l], widths[l + 1]);
             st = launch_layer(cur, cur_bf16, ld, W[l], wdtype, bias[l], B, widths[l], widths[l + 1],
-                              last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, partial, s);
+                              last ? (int)final_act : (int)hidden_act, dst, bf && !last, ldd, gemm_area,
+                              carries ? scan : nullptr, s);
+            if (carries) scan = nullptr;
         }
         if (st != REC_OK) return st;
         cur = dst;

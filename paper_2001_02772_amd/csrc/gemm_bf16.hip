@@ -3,275 +3,349 @@
 // This is the one genuinely dense, FLOP-heavy contraction of the models in Table I of the
 // DeepRecSys paper: the first Dense-FC layer of the MLP-dominated DLRM-RMC3 (thousands of dense
 // inputs into a 1024-wide layer; Section III-A: its run time is dominated by FC layers).
-// 128x128 output tile per block, four waves each owning a 64x64 quarter as 2x2
-// v_mfma_f32_32x32x16_bf16 tiles, k staged 64 at a time through double-buffered LDS with the
-// global loads of the following tiles in flight.  A batch of a thousand rows gives only 64 such
-// tiles for 256 CUs, so the reduction dimension is also split across blocks; the fp32 partial
-// tiles go to a workspace and a second small kernel adds them in a fixed order and applies bias
-// and activation, which keeps the result reproducible.
+//
+// Both operands are contiguous along k, so a 64-wide k slice of a row is one 128-byte line.  Tiles
+// go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, so the
+// register file holds accumulators and operand fragments only); a wave instruction moves 8 rows x
+// 128 bytes, and the 16-byte chunks of a row are XOR-swizzled with the row number -- applied on the
+// global side, because the LDS side of such a load is lane-linear -- so that the 16-byte fragment
+// reads of the 32x32x16 MFMA are bank-conflict free without padding.  A ring of NST stages keeps
+// several k slices in flight; the wave waits with explicit vmcnt counts, and the one barrier per
+// slice sits in the middle of the slice (NST >= 3) so the next slice's first fragments are read
+// while the current slice still multiplies.  Measured on the part: LDS delivers 128 bytes/clock per
+// CU, so a wave must own at least a 64x64 sub-tile (2x2 MFMA tiles) for the matrix cores not to wait
+// on fragment reads, and a CU fetches about 70-100 GB/s from L2, which is why the large-batch
+// variant uses 256x256 tiles.
+//
+// The tile shrinks with the batch so that there is about a block per CU: 256x256 (8 waves), 128x128,
+// 128x64 or 64x64 (4 waves).  At a batch of a thousand rows the 64x64 tiles re-fetch each operand
+// sixteen times from L2 and the layer is bound by what a CU can fetch, not by the matrix cores;
+// splitting k across blocks instead (128x128 tiles, partial tiles through memory, the last arrival
+// folding them) was measured no faster, because making the partial tiles visible across the XCDs'
+// separate L2s needs device-scope fences that cost more than the fetches they save.
 #include "rec_common.h"
+#include "scan_body.h"
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
 
-constexpr int GB_BM = 128, GB_BN = 128, GB_BK = 64;
-constexpr int GB_THREADS = 256;
-constexpr int GB_STAGES = 3;                              // k tiles of global loads in flight
-constexpr int GB_LD = GB_BK + 8;                          // padded LDS row in bf16 elements (144 B)
-constexpr int GB_TILE = (GB_BM + GB_BN) * GB_LD;          // elements per stage
+// 64 lanes x 16 bytes from global (uniform base + per-lane byte offset) to LDS: lane l's bytes land at
+// LDS address lds_off + 16 l.  Tracked by vmcnt like any vector load.
+__device__ __forceinline__ void lds_dma16(uint32_t lane_off, const void* base, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory");
+}
+// Wait until at most N of this wave's vector loads are outstanding, then meet the block's other
+// waves.  One asm statement with a memory clobber: no LDS access moves across it.
+template <int N>
+__device__ __forceinline__ void wait_loads_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+// The same with a count known only at run time (block-uniform): at most min(r, MAXR) groups of LPT loads.
+template <int LPT, int MAXR>
+__device__ __forceinline__ void wait_groups_barrier(int r) {
+    if constexpr (MAXR == 0) {
+        wait_loads_barrier<0>();
+    } else {
+        if (r >= MAXR) wait_loads_barrier<MAXR * LPT>();
+        else wait_groups_barrier<LPT, MAXR - 1>(r);
+    }
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_lds_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     const floatx2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));   // v_cvt_pk_bf16_f32, RNE
 }
 
-// Requires K % 64 == 0, lda % 4 == 0 (fp32 A) or % 8 == 0 (bf16 A), 16-byte aligned A and W.
-// grid = ceil(N/128) * ceil(M/128) * S blocks.  S == 1: writes act(acc + bias) to C.  S > 1: k part z
-// covers k in [z*K/S, (z+1)*K/S) and writes its raw fp32 tile to part[z][M][N].
-template <bool A_BF16>
-__global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(const void* __restrict__ Av, int64_t lda,
-                                                               const uint16_t* __restrict__ W,
-                                                               const float* __restrict__ bias, void* __restrict__ C,
-                                                               int c_bf16, int64_t ldc, float* __restrict__ part, int M,
-                                                               int N, int K, int S, int act) {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * GB_TILE];
+template <int BM_, int BN_, int WM_, int WN_, int NST_>
+struct GemmCfg {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NST = NST_;
+    static constexpr int NW = WM * WN, THREADS = 64 * NW;
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;          // MFMA tiles per wave
+    static constexpr int STAGE_BYTES = (BM + BN) * 128;                 // one 64-wide k slice of both operands
+    static constexpr int A_PER_WAVE = BM / 8 / NW, W_PER_WAVE = BN / 8 / NW;
+    static constexpr int LPT = A_PER_WAVE + W_PER_WAVE;                 // load instructions per wave per slice
+    static constexpr int ACC = TM * TN * 16;                            // accumulator floats per thread
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split evenly over the waves");
+    static_assert(NST * STAGE_BYTES <= 160 * 1024, "LDS capacity");
+    static_assert((NST - 1) * LPT < 64, "vmcnt is a 6-bit counter");
+};
+
+// Requires K % 64 == 0, 16-byte aligned A and W, lda and ldw multiples of 8, M*lda*2 and N*ldw*2
+// below 2^32.  grid = tiles_m * tiles_n blocks.
+template <class C, bool C_BF16>
+__global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                               const uint16_t* __restrict__ W, int64_t ldw,
+                                                               const float* __restrict__ bias, void* __restrict__ Cv,
+                                                               int64_t ldc, int M, int N, int K, int act) {
+    constexpr int BM = C::BM, BN = C::BN, NST = C::NST, TM = C::TM, TN = C::TN;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * C::STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
-    // Blocks are dealt to the 8 XCDs round-robin.  Renumber them so that XCD x works on a
-    // contiguous eighth of the (row tile, column tile, k part) list with the row tile slowest:
-    // the x rows of one row tile are then fetched into a single L2 and reused by all its column
-    // tiles there, instead of being fetched by eight L2s.
-    int blk = blockIdx.x;
+    const int wm = wave % C::WM, wn = wave / C::WM;
+
+    // Blocks are dealt to the 8 XCDs round-robin.  Renumber them so that XCD x works on a contiguous
+    // eighth of the (row tile, column tile) list, row tile slowest: a few whole row tiles per XCD, whose
+    // operand slices then live in that XCD's L2 and are shared by its CUs.
+    int o = blockIdx.x;
     {
         const int per = gridDim.x / 8;
-        if (blk < per * 8) blk = (blk % 8) * per + blk / 8;
+        if (o < per * 8) o = (o % 8) * per + o / 8;
     }
-    const int tiles_n = (N + GB_BN - 1) / GB_BN;
-    const int z = blk % S;
-    const int tile = blk / S;
-    const int m0 = (tile / tiles_n) * GB_BM, n0 = (tile % tiles_n) * GB_BN;
-    const int k_len = K / S;                              // host guarantees K % (S*64) == 0
-    const int k_begin = z * k_len;
-    const int n_tiles = k_len / GB_BK;
+    const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM, tiles = tiles_m * tiles_n;
+    const int tile = o < tiles ? o : tiles - 1;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int n_slices = K / 64;
 
-    // staging registers, GB_STAGES tiles deep: A tile 128x64 (fp32: 8 float4 per thread; bf16: 4 x 8
-    // elements), W tile 4 x 8 elements
-    struct StageRegs {
-        float4 ra[A_BF16 ? 1 : 8];
-        ushort8 rab[A_BF16 ? 4 : 1];
-        ushort8 rw[4];
-    };
-    StageRegs st[GB_STAGES];
-
-    auto load_tile = [&](StageRegs& r, int k0) __attribute__((always_inline)) {
-        if constexpr (A_BF16) {
-            const uint16_t* __restrict__ A = static_cast<const uint16_t*>(Av);
+    // Load instruction j of a wave covers tile rows (j NW + wave) 8 .. +8; lane l fetches, for row
+    // r = that + l/8, the chunk (l%8) ^ (r%8) and deposits it in slot l%8 of the row.  Rows past the
+    // matrix edge re-read the last row (a valid address); they only feed results that are not stored.
+    uint32_t offA[C::A_PER_WAVE], offW[C::W_PER_WAVE];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int f = tid + i * GB_THREADS, row = f >> 3, c = (f & 7) * 8;
-                const int gr = m0 + row;
-                r.rab[i] = *reinterpret_cast<const ushort8*>(A + (int64_t)(gr < M ? gr : 0) * lda + k0 + c);
-            }
-        } else {
-            const float* __restrict__ A = static_cast<const float*>(Av);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int f = tid + i * GB_THREADS, row = f >> 4, c = (f & 15) * 4;
-                const int gr = m0 + row;
-                r.ra[i] = *reinterpret_cast<const float4*>(A + (int64_t)(gr < M ? gr : 0) * lda + k0 + c);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = tid + i * GB_THREADS, row = f >> 3, c = (f & 7) * 8;
-            const int gn = n0 + row;
-            r.rw[i] = *reinterpret_cast<const ushort8*>(W + (int64_t)(gn < N ? gn : 0) * K + k0 + c);
-        }
-    };
-    // rows past M / N were read from row 0 (a valid address); they only feed accumulator rows /
-    // columns that are never stored, so no masking is needed
-    auto store_tile = [&](const StageRegs& r, int s) __attribute__((always_inline)) {
-        uint16_t* ta = lds + s * GB_TILE;
-        uint16_t* tw = ta + GB_BM * GB_LD;
-        if constexpr (A_BF16) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int f = tid + i * GB_THREADS, row = f >> 3, c = (f & 7) * 8;
-                *reinterpret_cast<ushort8*>(ta + row * GB_LD + c) = r.rab[i];
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int f = tid + i * GB_THREADS, row = f >> 4, c = (f & 15) * 4;
-                const uint2 o = make_uint2(pack_bf16(r.ra[i].x, r.ra[i].y), pack_bf16(r.ra[i].z, r.ra[i].w));
-                *reinterpret_cast<uint2*>(ta + row * GB_LD + c) = o;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = tid + i * GB_THREADS, row = f >> 3, c = (f & 7) * 8;
-            *reinterpret_cast<ushort8*>(tw + row * GB_LD + c) = r.rw[i];
-        }
-    };
-
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{0};
-
-    const int frag = (lane & 31) * GB_LD + (lane >> 5) * 8;
-    auto multiply_tile = [&](int cur) __attribute__((always_inline)) {
-        const uint16_t* ta = lds + cur * GB_TILE + (wm * 64) * GB_LD + frag;
-        const uint16_t* tw = lds + cur * GB_TILE + (GB_BM + wn * 64) * GB_LD + frag;
-#pragma unroll
-        for (int kc = 0; kc < GB_BK / 16; ++kc) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(ta + kc * 16);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(ta + 32 * GB_LD + kc * 16);
-            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(tw + kc * 16);
-            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(tw + 32 * GB_LD + kc * 16);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-        }
-    };
-    // Every load in the steady-state loop is unconditional (a tile index past the end re-reads the
-    // last tile and is never multiplied), so the number of loads in flight at each point is fixed
-    // and the hardware wait counters can let the younger GB_STAGES-1 tiles stay outstanding while
-    // the oldest is written to LDS.  Conditional loads would force a wait for all of them.
-    const int last_tile = n_tiles - 1;
-    auto tile_k = [&](int t) { return k_begin + (t < last_tile ? t : last_tile) * GB_BK; };
-#pragma unroll
-    for (int p = 0; p < GB_STAGES; ++p) load_tile(st[p], tile_k(p));
-    store_tile(st[0], 0);
-    __syncthreads();
-    const int full_groups = n_tiles / GB_STAGES;
-    for (int g = 0; g < full_groups; ++g) {
-#pragma unroll
-        for (int p = 0; p < GB_STAGES; ++p) {
-            const int it = g * GB_STAGES + p;
-            const int cur = it & 1;
-            load_tile(st[p], tile_k(it + GB_STAGES));           // stage p went to LDS one step ago
-            multiply_tile(cur);
-            // keep the conversion of the next tile (which waits for its loads) behind the multiply:
-            // hoisted above it, the wait would stall the matrix cores on memory latency
-            __builtin_amdgcn_sched_barrier(0);
-            store_tile(st[(p + 1) % GB_STAGES], cur ^ 1);       // tile it+1
-            __syncthreads();
-        }
+    for (int j = 0; j < C::A_PER_WAVE; ++j) {
+        const int r = (j * C::NW + wave) * 8 + (lane >> 3);
+        const int gr = min(m0 + r, M - 1);
+        offA[j] = (uint32_t)((int64_t)gr * lda * 2 + (((lane & 7) ^ (r & 7)) * 16));
     }
-    // the n_tiles % GB_STAGES tiles left over are already in st[0..] / LDS; no loads here
 #pragma unroll
-    for (int p = 0; p < GB_STAGES - 1; ++p) {
-        const int it = full_groups * GB_STAGES + p;
-        if (it < n_tiles) {
-            const int cur = it & 1;
-            multiply_tile(cur);
-            if (it + 1 < n_tiles) store_tile(st[p + 1], cur ^ 1);
-            __syncthreads();
+    for (int j = 0; j < C::W_PER_WAVE; ++j) {
+        const int r = (j * C::NW + wave) * 8 + (lane >> 3);
+        const int gr = min(n0 + r, N - 1);
+        offW[j] = (uint32_t)((int64_t)gr * ldw * 2 + (((lane & 7) ^ (r & 7)) * 16));
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    const unsigned char* gA = reinterpret_cast<const unsigned char*>(A);
+    const unsigned char* gW = reinterpret_cast<const unsigned char*>(W);
+    auto request = [&](int slice, int stage) __attribute__((always_inline)) {
+        const unsigned char* a = gA + (int64_t)slice * 128;
+        const unsigned char* w = gW + (int64_t)slice * 128;
+        const uint32_t sb = lds_base + stage * C::STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < C::A_PER_WAVE; ++j) lds_dma16(offA[j], a, sb + j * C::NW * 1024);
+#pragma unroll
+        for (int j = 0; j < C::W_PER_WAVE; ++j) lds_dma16(offW[j], w, sb + BM * 128 + j * C::NW * 1024);
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = floatx16{0};
+
+    // MFMA 32x32x16 operands: lane l supplies row l%32 and the 8 k values of chunk 2 kc + l/32.
+    const int ra = wm * (BM / C::WM) + (lane & 31), rw = wn * (BN / C::WN) + (lane & 31);
+    const int fa = ra & 7, fw = rw & 7, hi = lane >> 5;
+    bf16x8 af[2][TM], wf[2][TN];
+    auto load_frags = [&](int stage, int kc, int buf) __attribute__((always_inline)) {
+        const unsigned char* sa = lds + stage * C::STAGE_BYTES + ra * 128;
+        const unsigned char* sw = lds + stage * C::STAGE_BYTES + BM * 128 + rw * 128;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 4096 + (((2 * kc + hi) ^ fa) * 16));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(sw + j * 4096 + (((2 * kc + hi) ^ fw) * 16));
+    };
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+    };
+
+    if constexpr (NST >= 3) {
+        // Slice t lives in stage t % NST.  In the middle of slice t: slice t+1 has landed (own loads
+        // waited for, then the barrier), and every wave is past slice t-1, so its stage takes the request
+        // for slice t+NST-1.  The wait counts are the wave's own requests issued after the awaited one.
+#pragma unroll
+        for (int p = 0; p < NST - 1; ++p)
+            if (p < n_slices) request(p, p);
+        wait_groups_barrier<C::LPT, NST - 2>(n_slices - 1);          // slice 0 landed; up to NST-2 younger ones in flight
+        load_frags(0, 0, 0);
+        for (int t0 = 0; t0 < n_slices; t0 += NST) {
+#pragma unroll
+            for (int s = 0; s < NST; ++s) {
+                const int t = t0 + s;
+                if (t < n_slices) {
+                    load_frags(s, 1, 1);
+                    multiply(0);
+                    load_frags(s, 2, 0);
+                    multiply(1);
+                    if (t + 1 < n_slices) {
+                        // in flight: slices t+1 .. min(t+NST-2, n_slices-1); t+1 must be complete
+                        wait_groups_barrier<C::LPT, NST - 3>(n_slices - 2 - t);
+                        if (t + NST - 1 < n_slices) request(t + NST - 1, (s + NST - 1) % NST);
+                    }
+                    load_frags(s, 3, 1);
+                    multiply(0);
+                    if (t + 1 < n_slices) load_frags((s + 1) % NST, 0, 0);
+                    multiply(1);
+                }
+            }
+        }
+    } else {
+        // two stages: slice t+1 is requested as soon as every wave has left slice t-1
+        request(0, 0);
+        for (int t0 = 0; t0 < n_slices; t0 += 2) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int t = t0 + s;
+                if (t < n_slices) {
+                    wait_loads_lds_barrier<0>();
+                    if (t + 1 < n_slices) request(t + 1, s ^ 1);
+                    load_frags(s, 0, 0);
+                    load_frags(s, 1, 1);
+                    multiply(0);
+                    load_frags(s, 2, 0);
+                    multiply(1);
+                    load_frags(s, 3, 1);
+                    multiply(0);
+                    multiply(1);
+                }
+            }
         }
     }
 
-    // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, col l%32
+    // MFMA 32x32 accumulator layout: register v of lane l holds row 8 (v/4) + 4 (l/32) + v%4, column l%32.
+    // Bias values are fetched before the first store so that no load waits behind the stores.
+    typedef typename std::conditional<C_BF16, uint16_t, float>::type out_t;
+    out_t* Cp = static_cast<out_t*>(Cv);
+    float bv[TN];
+    int nn[TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int j = 0; j < TN; ++j) {
+        nn[j] = n0 + wn * (BN / C::WN) + j * 32 + (lane & 31);
+        bv[j] = nn[j] < N ? bias[nn[j]] : 0.f;
+    }
+    const bool relu = act == REC_ACT_RELU, sigm = act == REC_ACT_SIGMOID;
+    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-            if (n >= N) continue;
-            const float bv = (S == 1) ? bias[n] : 0.f;
+    for (int i = 0; i < TM; ++i) {
+        const int mb = m0 + wm * (BM / C::WM) + i * 32 + 4 * hi;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            out_t* col = Cp + nn[j];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m >= M) continue;
-                if (S == 1) {
-                    const float z = rec_apply_act(acc[i][j][v] + bv, act);
-                    if (c_bf16) static_cast<uint16_t*>(C)[(int64_t)m * ldc + n] = rec_f32_to_bf16_bits(z);
-                    else static_cast<float*>(C)[(int64_t)m * ldc + n] = z;
-                } else {
-                    part[((int64_t)z * M + m) * N + n] = acc[i][j][v];
+                const int m = mb + 8 * (v >> 2) + (v & 3);
+                float zv = acc[i][j][v] + bv[j];
+                if (relu) zv = fmaxf(zv, 0.f);
+                if (sigm) zv = 1.0f / (1.0f + expf(-zv));
+                if (full || (m < M && nn[j] < N)) {
+                    if constexpr (C_BF16) col[(int64_t)m * ldc] = (uint16_t)pack_bf16(zv, 0.f);
+                    else col[(int64_t)m * ldc] = zv;
                 }
             }
         }
     }
 }
 
-// C = act(sum_z part[z] + bias), z = 0, 1, ... in order.  One thread per 4 consecutive columns.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int S,
-                                                            const float* __restrict__ bias, void* __restrict__ C,
-                                                            int c_bf16, int64_t ldc, int M, int N, int act) {
-    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;      // quad index
-    const int nq = (N + 3) / 4;
-    if (q >= (int64_t)M * nq) return;
-    const int m = (int)(q / nq), n = (int)(q - (int64_t)m * nq) * 4;
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    const bool full = (n + 3 < N) && (N % 4 == 0);
-    for (int z = 0; z < S; ++z) {
-        const float* p = part + ((int64_t)z * M + m) * N + n;
-        if (full) {
-            const float4 v = *reinterpret_cast<const float4*>(p);
-            s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n + e < N) s[e] += p[e];
-        }
+// fp32 rows -> bf16 rows (round to nearest even), 8 elements per thread; the first `scan_tiles`
+// blocks do a bag-offsets scan instead.
+__global__ __launch_bounds__(SCAN_THREADS) void prepare_bf16_kernel(const float* __restrict__ x, int64_t ldx,
+                                                                    uint16_t* __restrict__ y, int64_t ldy, int32_t M,
+                                                                    int32_t K, const int32_t* __restrict__ len,
+                                                                    int64_t n_bags, int64_t* __restrict__ off, int vec_ok,
+                                                                    int scan_tiles) {
+    if ((int)blockIdx.x < scan_tiles) {
+        offsets_block(len, n_bags, off, vec_ok, (int)blockIdx.x, true);
+        return;
     }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (n + e < N) {
-            const float z = rec_apply_act(s[e] + bias[n + e], act);
-            if (c_bf16) static_cast<uint16_t*>(C)[(int64_t)m * ldc + n + e] = rec_f32_to_bf16_bits(z);
-            else static_cast<float*>(C)[(int64_t)m * ldc + n + e] = z;
-        }
+    const int k8 = K / 8;
+    const int64_t n8 = (int64_t)M * k8;
+    const int64_t step = (int64_t)(gridDim.x - scan_tiles) * SCAN_THREADS;
+    for (int64_t i = (int64_t)(blockIdx.x - scan_tiles) * SCAN_THREADS + threadIdx.x; i < n8; i += step) {
+        const int64_t m = i / k8;
+        const int c = (int)(i - m * k8) * 8;
+        const float4 a = *reinterpret_cast<const float4*>(x + m * ldx + c);
+        const float4 b = *reinterpret_cast<const float4*>(x + m * ldx + c + 4);
+        const uint4 o = make_uint4(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w), pack_bf16(b.x, b.y), pack_bf16(b.z, b.w));
+        *reinterpret_cast<uint4*>(y + m * ldy + c) = o;
     }
 }
+
+// Tile shapes, largest first; a shape is taken when it gives about a block per CU.
+typedef GemmCfg<256, 256, 4, 2, 2> Cfg256;      // 8 waves of 64x128, 2 stages of 64 KiB
+typedef GemmCfg<128, 128, 2, 2, 4> Cfg128;      // 4 waves of 64x64, 4 stages of 32 KiB
+typedef GemmCfg<128, 64, 2, 2, 5> Cfg128x64;    // 4 waves of 64x32, 5 stages of 24 KiB
+typedef GemmCfg<64, 64, 2, 2, 8> Cfg64;         // 4 waves of 32x32, 8 stages of 16 KiB
+
+constexpr int GEMM_MIN_BLOCKS = 200;      // about one block per CU
+
+int64_t tile_count(int M, int N, int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); }
 
 }  // namespace
 
-// Split factor for the cross-block k split: enough blocks for the 256 CUs, k parts of at least
-// 256 that are multiples of the 64-wide step.  Returns 0 if the large-tile kernel does not apply.
-int rec_gemm_bf16_split(int M, int N, int K) {
-    if (K % GB_BK != 0 || K < 256) return 0;
-    const int64_t tiles = (int64_t)((M + GB_BM - 1) / GB_BM) * ((N + GB_BN - 1) / GB_BN);
-    if (tiles < 64) return 0;                 // smaller layers do better on the 64x64 / 32x32 kernels
-    int S = 1;
-    while (S < 8 && tiles * S < 256 && K % (S * 2 * GB_BK) == 0 && K / (S * 2) >= 256) S *= 2;
-    return S;
+rec_gemm_plan rec_gemm_bf16_plan(int M, int N, int K) {
+    rec_gemm_plan p = {0, 0, 0};
+    if (M < 1 || N < 1 || K < 256 || K % 64 != 0) return p;
+    if ((int64_t)M * K * 2 >= (int64_t)1 << 32 || (int64_t)N * K * 2 >= (int64_t)1 << 32) return p;
+    const int shapes[4][2] = {{256, 256}, {128, 128}, {128, 64}, {64, 64}};
+    for (int i = 0; i < 4; ++i) {
+        const int64_t t = tile_count(M, N, shapes[i][0], shapes[i][1]);
+        // the smallest shape also serves layers that leave part of the device idle, down to a quarter
+        if (t >= GEMM_MIN_BLOCKS || (i == 3 && t >= 64)) {
+            p.bm = shapes[i][0];
+            p.bn = shapes[i][1];
+            p.tiles = (int)t;
+            return p;
+        }
+    }
+    return p;
 }
 
-size_t rec_gemm_bf16_partial_bytes(int M, int N, int K) {
-    const int S = rec_gemm_bf16_split(M, N, K);
-    return S > 1 ? rec_round_up((size_t)S * M * N * sizeof(float), 256) : 0;
+// Workspace of one layer launch: the bf16 copy of fp32 activations (none for bf16 input).
+size_t rec_gemm_bf16_workspace_bytes(int M, int N, int K, bool x_bf16) {
+    (void)N;
+    return x_bf16 ? 0 : rec_round_up((size_t)M * K * sizeof(uint16_t), 256);
 }
 
 rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const void* W, const float* bias, void* y,
-                                bool y_bf16, int64_t ldy, float* partial, int M, int N, int K, int act,
-                                hipStream_t s) {
-    const int S = rec_gemm_bf16_split(M, N, K);
-    if (S < 1) return REC_ERR_UNSUPPORTED;
-    if (S > 1 && !partial) return REC_ERR_WORKSPACE;
-    const dim3 grid((unsigned)(((N + GB_BN - 1) / GB_BN) * ((M + GB_BM - 1) / GB_BM) * S)), block(GB_THREADS);
-    const uint16_t* Wb = static_cast<const uint16_t*>(W);
-    if (x_bf16)
-        hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid, block, 0, s, x, ldx, Wb, bias, y, (int)y_bf16, ldy, partial, M, N,
-                           K, S, act);
-    else
-        hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid, block, 0, s, x, ldx, Wb, bias, y, (int)y_bf16, ldy, partial, M, N,
-                           K, S, act);
-    REC_CHECK_LAUNCH();
-    if (S > 1) {
-        const int64_t quads = (int64_t)M * ((N + 3) / 4);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, partial, S, bias,
-                           y, (int)y_bf16, ldy, M, N, act);
+                                bool y_bf16, int64_t ldy, void* workspace, int M, int N, int K, int act,
+                                const rec_scan_job* scan, hipStream_t s) {
+    const rec_gemm_plan p = rec_gemm_bf16_plan(M, N, K);
+    if (p.tiles == 0) return REC_ERR_UNSUPPORTED;
+    if (!workspace && !x_bf16) return REC_ERR_WORKSPACE;
+    uint16_t* xh = static_cast<uint16_t*>(workspace);
+
+    int scan_tiles = 0;
+    if (scan) {
+        scan_tiles = rec_scan_parallel_tiles(scan->n);
+        if (scan_tiles < 1) return REC_ERR_BAD_SHAPE;          // the caller launches such a scan itself
+    }
+    if (!x_bf16 || scan_tiles > 0) {
+        // one preparing launch: bf16 copy of the activations, and the scan if one rides along
+        const int64_t n8 = x_bf16 ? 0 : (int64_t)M * (K / 8);
+        int64_t blocks = (n8 + SCAN_THREADS - 1) / SCAN_THREADS;
+        blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+        hipLaunchKernelGGL(prepare_bf16_kernel, dim3((unsigned)(blocks + scan_tiles)), dim3(SCAN_THREADS), 0, s,
+                           static_cast<const float*>(x), ldx, xh, (int64_t)K, x_bf16 ? 0 : M, K,
+                           scan ? scan->lengths : nullptr, scan ? scan->n : 0, scan ? scan->offsets : nullptr,
+                           scan ? (int)rec_aligned(scan->lengths, 16) : 0, scan_tiles);
         REC_CHECK_LAUNCH();
     }
+    const uint16_t* Ab = x_bf16 ? static_cast<const uint16_t*>(x) : xh;
+    const int64_t lda = x_bf16 ? ldx : (int64_t)K;
+    const uint16_t* Wb = static_cast<const uint16_t*>(W);
+#define GEMM_GO(CFG)                                                                                                    \
+    do {                                                                                                                \
+        const dim3 grid((unsigned)p.tiles), block(CFG::THREADS);                                                        \
+        if (y_bf16)                                                                                                     \
+            hipLaunchKernelGGL((gemm_bf16_kernel<CFG, true>), grid, block, 0, s, Ab, lda, Wb, (int64_t)K, bias, y, ldy, M, N, K, act); \
+        else                                                                                                            \
+            hipLaunchKernelGGL((gemm_bf16_kernel<CFG, false>), grid, block, 0, s, Ab, lda, Wb, (int64_t)K, bias, y, ldy, M, N, K, act); \
+    } while (0)
+    if (p.bm == 256) GEMM_GO(Cfg256);
+    else if (p.bm == 128 && p.bn == 128) GEMM_GO(Cfg128);
+    else if (p.bm == 128) GEMM_GO(Cfg128x64);
+    else GEMM_GO(Cfg64);
+#undef GEMM_GO
+    REC_CHECK_LAUNCH();
     return REC_OK;
 }

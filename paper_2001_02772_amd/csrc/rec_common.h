@@ -109,8 +109,15 @@ rec_status rec_interact_padded(const float* vecs, int32_t B, int32_t V, int32_t 
                                int32_t zero_to, void* stream);
 
 // ---- large bf16 layers (gemm_bf16.hip) --------------------------------------------------------
-int rec_gemm_bf16_split(int M, int N, int K);                    // 0: kernel does not apply
-size_t rec_gemm_bf16_partial_bytes(int M, int N, int K);         // fp32 partial tiles for the k split
+struct rec_gemm_plan {
+    int bm, bn;     // output tile (rows x columns)
+    int tiles;      // output tiles = blocks; 0: the kernel does not apply to this layer
+};
+rec_gemm_plan rec_gemm_bf16_plan(int M, int N, int K);
+// Bytes of workspace one such layer needs (the bf16 copy of fp32 activations); grows with M.
+size_t rec_gemm_bf16_workspace_bytes(int M, int N, int K, bool x_bf16);
+// y = act(x W^T + bias); x fp32 (copied to bf16 first) or bf16.  `scan` (may be NULL, must have
+// parallel tiles): run this offsets scan inside the layer's preparing launch.
 rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const void* W, const float* bias, void* y,
-                                bool y_bf16, int64_t ldy, float* partial, int M, int N, int K, int act,
-                                hipStream_t s);
+                                bool y_bf16, int64_t ldy, void* workspace, int M, int N, int K, int act,
+                                const rec_scan_job* scan, hipStream_t s);

@@ -369,3 +369,23 @@ def test_host_checkable_errors(rec):
         rec.interact(dev(np.zeros((2, 3, 8), np.float32)), out=torch.empty((2, 4), device="cuda"), ldo=4)
     assert e.value.status == rec.ERR_BAD_SHAPE
     assert rec.status_string(rec.ERR_INDEX_RANGE) == "REC_ERR_INDEX_RANGE"
+
+
+@pytest.mark.parametrize("widths,B", [((2560, 1024), 2048), ((2560, 1024), 4000), ((2560, 1024), 16300),
+                                      ((256, 4136), 3300), ((2560, 1024, 8), 4000), ((1024, 512, 1), 5000)])
+def test_mlp_bf16_large_batches_sampled_rows(rec, widths, B):
+    """Batches that put the wide layer on the larger tile shapes (128x64, 128x128, 256x256, ragged in
+    both directions).  The oracle computes a sample of the rows -- rows are independent -- taken from
+    the first tile, the ragged last tile and in between."""
+    oracle.set_threads(16)
+    p = synth.mlp_params(widths, stack=5)
+    g = np.random.default_rng(B)
+    x = g.normal(size=(B, widths[0])).astype(np.float32)
+    rows = np.unique(np.concatenate([np.arange(40), np.arange(B - 70, B), g.integers(0, B, size=150)]))
+    W, b = [rec.f32_to_bf16(dev(w)) for w in p.W], [dev(v) for v in p.b]
+    final = rec.ACT_SIGMOID if widths[-1] == 1 else rec.ACT_RELU
+    got = rec.mlp_forward(W, b, dev(x), rec.ACT_RELU, final, wdtype=rec.BF16).cpu().numpy()
+    want = oracle.mlp(x[rows], p.W, p.b, rec.ACT_RELU, final, bf16=True)
+    assert got.shape == (B, widths[-1])
+    assert_close(got[rows], want, TOL_BF16, f"bf16 MLP {widths} at B={B}, {rows.size} sampled rows")
+    assert np.isfinite(got).all()
