@@ -20,10 +20,26 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X fp32 matrix, published
 
-# HBM bytes per launch of the pooling kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled
-# by a copy-shaped reference dispatch (see profiles/sls_kernel_rmc2_counters.md).  Valid for the
-# sls_kernel these were taken with; set an entry to None when that kernel changes.
-SLS_COUNTED_TRAFFIC_BYTES = {"rmc2": 368.5e6, "rmc2-uniform": 824.2e6}
+# Bytes the pooling kernel reads from and writes to memory per launch, from rocprofv3 L2 request
+# counters, live in a JSON block of this tracked summary together with the hash of the kernel source
+# they were taken with; a changed kernel source makes them void (reported as null).
+SLS_COUNTER_PROFILE = os.path.join("profiles", "sls_kernel_rmc2_counters.md")
+SLS_SOURCE = os.path.join("paper_2001_02772_amd", "csrc", "sls.hip")
+
+
+def counted_sls_traffic(workload):
+    """(bytes per launch or None, where it came from)."""
+    import hashlib
+    import re
+    try:
+        text = open(os.path.join(ROOT, SLS_COUNTER_PROFILE)).read()
+        block = json.loads(re.search(r"```json\s*(\{.*?\})\s*```", text, re.S).group(1))
+        sha = hashlib.sha256(open(os.path.join(ROOT, SLS_SOURCE), "rb").read()).hexdigest()
+    except (OSError, AttributeError, ValueError):
+        return None, f"{SLS_COUNTER_PROFILE}: not readable"
+    if block.get("sls_hip_sha256") != sha:
+        return None, f"{SLS_COUNTER_PROFILE}: taken with another version of {SLS_SOURCE}, void"
+    return block.get("traffic_bytes_per_launch", {}).get(workload), SLS_COUNTER_PROFILE
 
 
 def parse():
@@ -35,6 +51,11 @@ def parse():
     ap.add_argument("--batches", type=int, default=16, help="distinct pre-generated batches rotated through")
     ap.add_argument("--streams", type=int, default=4,
                     help="streams the timed steps rotate over (1 = one batch at a time)")
+    ap.add_argument("--repeats", type=int, default=5, help="the timed block of --steps steps is run this often; the median is reported")
+    ap.add_argument("--only-sls", action="store_true",
+                    help="set-up, then only launches of the pooling kernel (workload's indices, then uniform ones): for counter runs")
+    ap.add_argument("--only-mfma", action="store_true",
+                    help="only the bf16 FC layers of the MLP-dominated model at batch 1024 / 4096 / 16384: for counter runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-batch-size", action="store_true",
                     help="skip the short runs at sub-batch sizes 16/64/256 (keeps every launch of a profile at full batch)")
@@ -56,28 +77,40 @@ def sls_algorithmic_bytes(cfg, n_indices, B):
     return n_indices * (4 * cfg.D + 4) + cfg.T * B * (4 + 4 * cfg.D)
 
 
-def time_steps(fn, steps, warmup, torch):
+def time_steps(fn, steps, warmup, torch, repeats=1):
     for i in range(warmup):
         fn(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        fn(i)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    out = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) / steps)
+    return out[0] if repeats == 1 else out
 
 
-def time_many(model, rec, reqs, probs, streams, steps, warmup, torch):
-    """K forward passes enqueued by one library call, request i on stream i % S; seconds per step."""
+def time_many(model, rec, reqs, probs, streams, steps, warmup, torch, repeats=1):
+    """K forward passes enqueued by one library call, request i on stream i % S; seconds per step,
+    one figure per repeat of the K-step block (each bracketed by a device synchronisation)."""
     pick = lambda n: ([reqs[i % len(reqs)] for i in range(n)], [probs[i % len(probs)] for i in range(n)])
     timed = rec.ForwardMany(model, *pick(steps), streams)
     if warmup > 0:
         rec.ForwardMany(model, *pick(warmup), streams, workspaces=timed.ws).launch()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    timed.launch()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    out = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        timed.launch()
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) / steps)
+    return out
+
+
+def median(v):
+    v = sorted(v)
+    return v[len(v) // 2]
 
 
 def event_time(fn, steps, warmup, torch):
@@ -107,6 +140,7 @@ def cpu_baseline(cfg, batch):
         assert st == oracle.OK
         return p
 
+    # one GPU's share of the host is 16 cores whatever the host shows; use those (all of them on a smaller host)
     cores = min(16, os.cpu_count() or 1)
     oracle.set_threads(cores)
     oracle_forward(cfg, tables, batch, indices=idx)               # warm-up
@@ -128,11 +162,85 @@ def cpu_baseline(cfg, batch):
             cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
     except OSError:
         pass
-    return {"value": batch.B / mean, "unit": "samples/s", "cores": cores, "kind": "oracle", "cpu_model": cpu_model,
+    return {"value": batch.B / mean, "unit": "samples/s", "cores": cores, "host_cpus": os.cpu_count(), "kind": "oracle",
+            "cpu_model": cpu_model,
             "sample": f"one full {cfg.name} batch of {batch.B} samples, whole forward, repeated {len(runs)} times "
                       f"(about 8 s) on {cores} threads; value = mean rate",
             "best_value": batch.B / min(runs),
             "single_thread_value": batch.B / (sum(singles) / len(singles))}, p_all
+
+
+def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch, np, workload_name):
+    """The fused gather-and-pool kernel alone between two events on its launch stream, over the given
+    batches.  `achieved` / `frac` count only bytes that cross the memory side of the L2s (request
+    counters of a tracked profile, else the compulsory bytes a batch cannot avoid), so the fraction is
+    an HBM fraction; the algorithmic rate, which counts every looked-up row whether or not a cache
+    served it, is reported beside it."""
+    V = cfg.T + 1
+    offs = [rec.sls_offsets(d.lengths) for d in dbs]
+    vecs = torch.empty((cfg.B, V, cfg.D), dtype=torch.float32, device="cuda")
+
+    def sls_only(i):
+        d = dbs[i % len(dbs)]
+        rec.sls_forward_offsets(model_tables, d.indices, offs[i % len(dbs)], d.B, out=vecs[:, 1:, :],
+                                out_stride_b=V * cfg.D, out_stride_t=cfg.D)
+
+    sec = event_time(sls_only, steps, warmup, torch)
+    used = [dbs[i % len(dbs)].n_indices for i in range(steps)]
+    alg = float(np.mean([sls_algorithmic_bytes(cfg, n, cfg.B) for n in used]))
+    # compulsory traffic: distinct rows one batch touches (x row bytes) + its indices, offsets and pooled rows
+    hb = host_batches[0]
+    off = np.concatenate([[0], np.cumsum(hb.lengths, dtype=np.int64)])
+    distinct = int(sum(np.unique(hb.indices[off[t * cfg.B]:off[(t + 1) * cfg.B]]).size for t in range(cfg.T)))
+    compulsory = distinct * 4 * cfg.D + hb.indices.size * 4 + cfg.T * cfg.B * (8 + 4 * cfg.D)
+    traffic, source = counted_sls_traffic(workload_name)
+    hbm_bytes = traffic if traffic else compulsory
+    r = {"bound": "hbm", "kernel": "sls_kernel", "achieved": hbm_bytes / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": hbm_bytes / sec / 1e9 / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
+         "achieved_basis": ("bytes through the memory side of the L2s per launch (request counters)" if traffic else
+                            "compulsory bytes per launch (distinct rows + indices + offsets + output): a lower bound, no valid counter figure"),
+         "us_per_launch": sec * 1e6, "algorithmic_bytes_per_launch": alg,
+         "achieved_algorithmic": alg / sec / 1e9, "frac_algorithmic": alg / sec / 1e9 / HBM_PEAK_GBS,
+         "algorithmic_note": "every looked-up row counted once per lookup; includes rows served by L2, so it may exceed the HBM peak",
+         "distinct_rows_per_batch": distinct, "compulsory_bytes_per_launch": compulsory}
+    if traffic:
+        r["cache_served_fraction"] = 1.0 - traffic / alg
+    return r
+
+
+def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384)):
+    """The FC layers of the MLP-dominated model (rmc3 shape: 2560-1024-256-32 and 87-512-256-1, bf16
+    operands, fp32 accumulate) through rec_mlp_forward with resident random inputs: the first (widest)
+    layer alone at several batch sizes and both stacks at the model's batch.  Every figure is all-in:
+    fp32 activations in, the bf16 copy, the matrix kernel(s), fp32 out."""
+    cfg = synth.CONFIGS["rmc3"]
+    pb, pt = synth.mlp_params(cfg.bottom, 0), synth.mlp_params(cfg.top, 1)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Wb, bb = [rec.f32_to_bf16(dev(w)) for w in pb.W], [dev(v) for v in pb.b]
+    Wt, bt = [rec.f32_to_bf16(dev(w)) for w in pt.W], [dev(v) for v in pt.b]
+    F, n1 = cfg.bottom[0], cfg.bottom[1]
+
+    def run(Ws, bs, B, final_act, n):
+        widths = [Ws[0].shape[1]] + [w.shape[0] for w in Ws]
+        x = torch.randn((B, widths[0]), dtype=torch.float32, device="cuda")
+        y = torch.empty((B, widths[-1]), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(256, rec.mlp_workspace_bytes(widths, B, rec.BF16)), dtype=torch.uint8, device="cuda")
+        sec = event_time(lambda i: rec.mlp_forward(Ws, bs, x, rec.ACT_RELU, final_act, wdtype=rec.BF16, y=y, ldy=widths[-1],
+                                                   workspace=ws), n, warmup, torch)
+        fl = 2.0 * B * sum(widths[l] * widths[l + 1] for l in range(len(Ws)))
+        return {"us": sec * 1e6, "flops": fl, "tflops": fl / sec / 1e12, "frac": fl / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    sweep = {str(B): run(Wb[:1], bb[:1], B, rec.ACT_RELU, steps if B <= 4096 else max(20, steps // 4)) for B in batches}
+    l1 = sweep[str(cfg.B)]
+    bottom, top = run(Wb, bb, cfg.B, rec.ACT_RELU, steps), run(Wt, bt, cfg.B, rec.ACT_SIGMOID, steps)
+    both = {"us": bottom["us"] + top["us"], "flops": bottom["flops"] + top["flops"]}
+    both["tflops"] = both["flops"] / both["us"] / 1e6
+    both["frac"] = both["tflops"] / MFMA_BF16_PEAK_TFLOPS
+    return {"bound": "mfma", "kernel": "prepare_bf16_kernel + gemm_bf16_ks_kernel / gemm_bf16_kernel", "achieved": l1["tflops"],
+            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": l1["frac"], "traffic": None, "us_per_launch": l1["us"],
+            "flops_per_launch": l1["flops"],
+            "layer": f"{cfg.B}x{F} . ({n1}x{F})^T bf16 operands, fp32 accumulate; fp32 in and out through rec_mlp_forward",
+            "batch_sweep": sweep, "stacks": {"bottom": bottom, "top": top, "both": both}}
 
 
 def main():
@@ -152,6 +260,9 @@ def main():
     # ones the runtime spreads over distinct hardware queues
     pool = rec.StreamPool(a.streams)
     streams = pool.streams
+    if a.only_mfma:
+        print(json.dumps({"mfma_roofline": mfma_roofline(rec, synth, torch, a.steps, a.warmup)}))
+        return
     cfg = synth.CONFIGS[a.workload]
     t_setup = time.perf_counter()
     model = workload.device_model(cfg)
@@ -161,6 +272,25 @@ def main():
     probs = [torch.empty(cfg.B, dtype=torch.float32, device="cuda") for _ in dbs]
     ws = model.workspace(cfg.B)
     setup_s = time.perf_counter() - t_setup
+    torch.cuda.synchronize()            # set-up (on torch's stream) is complete before the pool's streams start
+
+    # the uniform-index control of the embedding-dominated model: same tables, same bag lengths' law
+    uniform = None
+    if cfg.name == "rmc2":
+        ucfg = synth.CONFIGS["rmc2-uniform"]
+        ugen = synth.BatchGenerator(ucfg)
+        uhost = [ugen.batch(k) for k in range(4)]
+        uniform = (ucfg, [workload.DeviceBatch(b) for b in uhost], uhost)
+
+    if a.only_sls:
+        out = {"roofline": sls_roofline(cfg, rec, model.tables, dbs, host_batches, a.steps, a.warmup, torch, np, cfg.name)}
+        if uniform:
+            out["roofline_uniform"] = sls_roofline(uniform[0], rec, model.tables, uniform[1], uniform[2], a.steps, a.warmup,
+                                                   torch, np, "rmc2-uniform")
+        if a.copy_calibration:
+            out["copy_calibration"] = copy_calibration(cfg, model, rec, torch)
+        print(json.dumps(out))
+        return
 
     def step(i):
         d = dbs[i % len(dbs)]
@@ -168,9 +298,11 @@ def main():
 
     # Headline: K steps over S streams (request i on stream i % S), so that the latency-bound
     # kernels of one batch run in the gaps of another; the single-stream figure (one batch at a
-    # time, the latency view) is reported next to it.
-    torch.cuda.synchronize()            # set-up (on torch's stream) is complete before the pool's streams start
-    sec_single = time_steps(step, a.steps, a.warmup, torch)
+    # time, the latency view) is reported next to it.  The K-step block is timed `repeats` times,
+    # each between device synchronisations; the median is the reported figure.
+    single_runs = time_steps(step, a.steps, a.warmup, torch, repeats=max(1, a.repeats))
+    single_runs = single_runs if isinstance(single_runs, list) else [single_runs]
+    sec_single = median(single_runs)
     lat = []                                   # one step at a time, enqueue to completion on the host clock
     for i in range(a.steps):
         t0 = time.perf_counter()
@@ -178,37 +310,13 @@ def main():
         torch.cuda.synchronize()
         lat.append(time.perf_counter() - t0)
     lat.sort()
-    sec = time_many(model, rec, dbs, probs, streams, a.steps, a.warmup, torch) if a.streams > 1 else sec_single
+    many_runs = (time_many(model, rec, dbs, probs, streams, a.steps, a.warmup, torch, repeats=max(1, a.repeats))
+                 if a.streams > 1 else single_runs)
+    sec = median(many_runs)
     value = cfg.B / sec
 
-    # dominant kernel: the fused gather-and-pool, timed alone between events on its stream
-    offs = [rec.sls_offsets(d.lengths) for d in dbs]
-    V = cfg.T + 1
-    vecs = torch.empty((cfg.B, V, cfg.D), dtype=torch.float32, device="cuda")
-
-    def sls_only(i):
-        d = dbs[i % len(dbs)]
-        rec.sls_forward_offsets(model.tables, d.indices, offs[i % len(dbs)], d.B, out=vecs[:, 1:, :],
-                                out_stride_b=V * cfg.D, out_stride_t=cfg.D)
-
-    sls_sec = event_time(sls_only, a.steps, a.warmup, torch)
-    used = [dbs[i % len(dbs)].n_indices for i in range(a.steps)]
-    sls_bytes = float(np.mean([sls_algorithmic_bytes(cfg, n, cfg.B) for n in used]))
-    sls_gbs = sls_bytes / sls_sec / 1e9
-    roofline = {"bound": "hbm", "kernel": "sls_kernel", "achieved": sls_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": sls_gbs / HBM_PEAK_GBS, "traffic": SLS_COUNTED_TRAFFIC_BYTES.get(cfg.name), "us_per_launch": sls_sec * 1e6,
-                "algorithmic_bytes_per_launch": sls_bytes}
-
-    # compulsory traffic: distinct rows one batch touches (x row bytes), from the generated indices
-    hb = host_batches[0]
-    off = np.concatenate([[0], np.cumsum(hb.lengths, dtype=np.int64)])
-    distinct = int(sum(np.unique(hb.indices[off[t * cfg.B]:off[(t + 1) * cfg.B]]).size for t in range(cfg.T)))
-    roofline["distinct_rows_per_batch"] = distinct
-    roofline["compulsory_row_bytes_per_batch"] = distinct * 4 * cfg.D
-    if roofline["traffic"]:
-        # share of the algorithmic bytes that did not come from HBM (served by L2 / Infinity Cache)
-        roofline["cache_served_fraction"] = 1.0 - roofline["traffic"] / sls_bytes
-        roofline["hbm_gbs_counted"] = roofline["traffic"] / sls_sec / 1e9
+    roofline = sls_roofline(cfg, rec, model.tables, dbs, host_batches, a.steps, a.warmup, torch, np, cfg.name)
+    sls_gbs = roofline["achieved_algorithmic"]
 
     # the two FC stacks timed alone (all their launches between two events): achieved FLOP/s.
     # (Through rec_mlp_forward with the caller's weights: inside the model the first predictor layer
@@ -236,33 +344,6 @@ def main():
                        "peak_tflops": peak_tf,
                        "frac": sum(s["flops"] for s in both) / sum(s["us"] for s in both) / 1e6 / peak_tf}
 
-    sls_roofline = roofline
-    if cfg.bf16:
-        # MLP-dominated workload: the dominant kernel is the first (widest) Dense-FC layer, a bf16
-        # MFMA contraction [B x F] . [n1 x F]^T.  Timed alone between events: the layer call launches
-        # the tiled GEMM and, when k is split across blocks, the small kernel that folds the partials.
-        # (a model without a dense stack: the first predictor layer, fed a resident random input)
-        if model.bottom_W:
-            W0, b0, xs = model.bottom_W[0], model.bottom_b[0], [d.dense for d in dbs]
-        else:
-            W0, b0 = model.top_W[0], model.top_b[0]
-            xs = [torch.randn((cfg.B, W0.shape[1]), dtype=torch.float32, device="cuda")]
-        n1, F = W0.shape
-        y1 = torch.empty((cfg.B, n1), dtype=torch.float32, device="cuda")
-        ws1 = torch.empty(max(256, rec.mlp_workspace_bytes([F, n1], cfg.B, rec.BF16)), dtype=torch.uint8, device="cuda")
-
-        def layer1(i):
-            rec.mlp_forward([W0], [b0], xs[i % len(xs)], rec.ACT_RELU, rec.ACT_RELU, wdtype=rec.BF16, y=y1,
-                            ldy=n1, workspace=ws1)
-
-        l1_sec = event_time(layer1, a.steps, a.warmup, torch)
-        flops = 2.0 * cfg.B * F * n1
-        tf = flops / l1_sec / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (+ splitk_reduce_kernel)", "achieved": tf,
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                    "us_per_launch": l1_sec * 1e6, "flops_per_launch": flops,
-                    "layer": f"{cfg.B}x{F} . ({n1}x{F})^T bf16 operands, fp32 accumulate"}
-
     # samples/s per sub-batch size (the batch sizes of the query-size sweep)
     per_b = {}
     for Bs in synth.SWEEP_BATCH_SIZES:
@@ -276,8 +357,8 @@ def main():
             model.forward(d.dense, d.indices, d.lengths, Bs, prob=probs[0], workspace=ws)
 
         s1 = time_steps(sub_step, max(50, a.steps // 2), 10, torch)
-        s = time_many(model, rec, subs, [probs[0][:Bs].clone() for _ in subs], streams, max(50, a.steps // 2), 10,
-                      torch) if a.streams > 1 else s1
+        s = median(time_many(model, rec, subs, [probs[0][:Bs].clone() for _ in subs], streams, max(50, a.steps // 2), 10,
+                             torch, repeats=3)) if a.streams > 1 else s1
         per_b[str(Bs)] = {"samples_per_s": Bs / s, "us_per_batch": s * 1e6,
                           "single_stream": {"samples_per_s": Bs / s1, "us_per_batch": s1 * 1e6}}
 
@@ -291,35 +372,28 @@ def main():
                       "dim": cfg.D, "lookups_per_bag": f"U{{{cfg.len_lo}..{cfg.len_hi}}}", "indices": cfg.index_dist,
                       "bottom": list(cfg.bottom), "top": list(cfg.top), "interaction": cfg.interaction,
                       "distinct_batches": len(dbs), "streams": a.streams},
+           "timing": {"repeats": len(many_runs), "ms_per_step_each_repeat": [r * 1e3 for r in many_runs],
+                      "reported": "median over the repeats of the timed block of `steps` steps"},
            "single_stream": {"value": cfg.B / sec_single, "ms_per_step": sec_single * 1e3,
+                             "ms_per_step_each_repeat": [r * 1e3 for r in single_runs],
                              "latency_ms_median": lat[len(lat) // 2] * 1e3, "latency_ms_min": lat[0] * 1e3},
-           "sls_gbs": sls_gbs, "per_batch_size": per_b, "roofline": roofline, "fc_stacks": stacks, "setup_s": setup_s}
-    if roofline is not sls_roofline:
-        out["sls_roofline"] = sls_roofline
+           "sls_gbs": sls_gbs, "per_batch_size": per_b, "fc_stacks": stacks, "setup_s": setup_s}
+    if cfg.bf16:
+        # MLP-dominated workload: the dominant kernel is the first (widest) Dense-FC layer
+        out["roofline"] = mfma_roofline(rec, synth, torch, a.steps, a.warmup) if cfg.name == "rmc3" else None
+        out["sls_roofline"] = roofline
+        if out["roofline"] is None:
+            out["roofline"] = roofline
+    else:
+        out["roofline"] = roofline
+    if uniform:
+        out["roofline_uniform"] = sls_roofline(uniform[0], rec, model.tables, uniform[1], uniform[2], a.steps, a.warmup, torch,
+                                               np, "rmc2-uniform")
+        # the other target of this build: bf16 MFMA rate of the MLP-dominated model's FC layers
+        out["mfma_roofline"] = mfma_roofline(rec, synth, torch, a.steps, a.warmup)
 
     if a.copy_calibration:
-        # Reference dispatches of known size for scaling FETCH_SIZE / WRITE_SIZE:
-        # (1) the pooling kernel itself streaming a table once -- one table, bag i = rows 4i..4i+3
-        #     (four lookups per bag keep it on sls_kernel, not on the short-bag kernel), so it reads n
-        #     rows (+ n indices, n/4+1 offsets) and writes n/4 rows with the request pattern of the real run;
-        # (2) the runtime's device-to-device copy of 256 MiB.
-        n = min(cfg.R, 500_000) // 4 * 4
-        nb = n // 4
-        one = rec.Tables([model.tables.tensors[0]])
-        idx = torch.arange(n, dtype=torch.int32, device="cuda")
-        off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * 4
-        dst_rows = torch.empty((nb, 1, cfg.D), dtype=torch.float32, device="cuda")
-        for _ in range(3):
-            rec.sls_forward_offsets(one, idx, off, nb, out=dst_rows, out_stride_b=cfg.D, out_stride_t=cfg.D)
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        out["copy_calibration"] = {"sls_as_copy": {"grid_threads": ((nb + 3) // 4) * 256,
-                                                   "read_bytes": n * (4 * cfg.D + 4) + 8 * (nb + 1),
-                                                   "write_bytes": nb * 4 * cfg.D},
-                                   "memcpy_d2d_bytes": int(src.numel())}
+        out["copy_calibration"] = copy_calibration(cfg, model, rec, torch)
 
     if a.sweep:
         out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
@@ -343,6 +417,30 @@ def main():
         p_gpu = probs[0].cpu().numpy()
         out["max_abs_diff_vs_oracle"] = float(np.max(np.abs(p_gpu - p_cpu)))
     print(json.dumps(out))
+
+
+def copy_calibration(cfg, model, rec, torch):
+    """Reference dispatches of known size for checking memory counters:
+    (1) the pooling kernel itself streaming a table once -- one table, bag i = rows 4i..4i+3
+        (four lookups per bag keep it on sls_kernel, not on the short-bag kernel), so it reads n
+        rows (+ n indices, n/4+1 offsets) and writes n/4 rows with the request pattern of the real run;
+    (2) the runtime's device-to-device copy of 256 MiB."""
+    n = min(cfg.R, 500_000) // 4 * 4
+    nb = n // 4
+    one = rec.Tables([model.tables.tensors[0]])
+    idx = torch.arange(n, dtype=torch.int32, device="cuda")
+    off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * 4
+    dst_rows = torch.empty((nb, 1, cfg.D), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        rec.sls_forward_offsets(one, idx, off, nb, out=dst_rows, out_stride_b=cfg.D, out_stride_t=cfg.D)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    return {"sls_as_copy": {"grid_threads": ((nb + 3) // 4) * 256, "read_bytes": n * (4 * cfg.D + 4) + 8 * (nb + 1),
+                            "write_bytes": nb * 4 * cfg.D},
+            "memcpy_d2d_bytes": int(src.numel())}
 
 
 def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np):

@@ -78,6 +78,44 @@ struct GemmCfg {
     static_assert((NST - 1) * LPT < 64, "vmcnt is a 6-bit counter");
 };
 
+// act(acc + bias) for a wave's TM x TN MFMA tiles whose top-left element is (row0, col0).
+// MFMA 32x32 accumulator layout: register v of lane l holds row 8 (v/4) + 4 (l/32) + v%4, column l%32.
+// Bias values are fetched before the first store so that no load waits behind the stores.
+template <bool C_BF16, int TM, int TN>
+__device__ __forceinline__ void store_tiles(const floatx16 (&acc)[TM][TN], const float* __restrict__ bias,
+                                            void* __restrict__ Cv, int64_t ldc, int M, int N, int row0, int col0, bool full,
+                                            int lane, int act) {
+    typedef typename std::conditional<C_BF16, uint16_t, float>::type out_t;
+    out_t* Cp = static_cast<out_t*>(Cv);
+    float bv[TN];
+    int nn[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        nn[j] = col0 + j * 32 + (lane & 31);
+        bv[j] = nn[j] < N ? bias[nn[j]] : 0.f;
+    }
+    const bool relu = act == REC_ACT_RELU, sigm = act == REC_ACT_SIGMOID;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int mb = row0 + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            out_t* col = Cp + nn[j];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mb + 8 * (v >> 2) + (v & 3);
+                float zv = acc[i][j][v] + bv[j];
+                if (relu) zv = fmaxf(zv, 0.f);
+                if (sigm) zv = 1.0f / (1.0f + expf(-zv));
+                if (full || (m < M && nn[j] < N)) {
+                    if constexpr (C_BF16) col[(int64_t)m * ldc] = (uint16_t)pack_bf16(zv, 0.f);
+                    else col[(int64_t)m * ldc] = zv;
+                }
+            }
+        }
+    }
+}
+
 // Requires K % 64 == 0, 16-byte aligned A and W, lda and ldw multiples of 8, M*lda*2 and N*ldw*2
 // below 2^32.  grid = tiles_m * tiles_n blocks.
 template <class C, bool C_BF16>
@@ -212,38 +250,114 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(const uint16_t* _
         }
     }
 
-    // MFMA 32x32 accumulator layout: register v of lane l holds row 8 (v/4) + 4 (l/32) + v%4, column l%32.
-    // Bias values are fetched before the first store so that no load waits behind the stores.
-    typedef typename std::conditional<C_BF16, uint16_t, float>::type out_t;
-    out_t* Cp = static_cast<out_t*>(Cv);
-    float bv[TN];
-    int nn[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        nn[j] = n0 + wn * (BN / C::WN) + j * 32 + (lane & 31);
-        bv[j] = nn[j] < N ? bias[nn[j]] : 0.f;
+    store_tiles<C_BF16, TM, TN>(acc, bias, Cv, ldc, M, N, m0 + wm * (BM / C::WM), n0 + wn * (BN / C::WN),
+                                (m0 + BM <= M) && (n0 + BN <= N), lane, act);
+}
+
+// The smallest tile, 64x64, with the four waves splitting k instead of the tile: wave w multiplies the
+// whole tile (2x2 MFMA tiles) for k chunk w of every 64-wide slice, so a slice costs 16 KiB of fragment
+// reads instead of 32 (with the 16 KiB the loads write, LDS traffic per slice drops by a third, and at
+// this tile size LDS is what the matrix cores wait for).  The four partial tiles meet in LDS at the end
+// and are added in wave order, each wave finishing one 32x32 quarter.  Same requirements as above.
+template <int NST, bool C_BF16>
+__global__ __launch_bounds__(256) void gemm_bf16_ks_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                          const uint16_t* __restrict__ W, int64_t ldw,
+                                                          const float* __restrict__ bias, void* __restrict__ Cv, int64_t ldc,
+                                                          int M, int N, int K, int act) {
+    constexpr int BM = 64, BN = 64, STAGE_BYTES = (BM + BN) * 128, LPT = 4;
+    static_assert(NST % 2 == 0 && NST >= 4 && NST * STAGE_BYTES >= 4 * 64 * 64 * 4, "ring doubles as the fold buffer");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int o = blockIdx.x;
+    {
+        const int per = gridDim.x / 8;
+        if (o < per * 8) o = (o % 8) * per + o / 8;
     }
-    const bool relu = act == REC_ACT_RELU, sigm = act == REC_ACT_SIGMOID;
-    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
+    const int tiles_n = (N + BN - 1) / BN;
+    const int m0 = (o / tiles_n) * BM, n0 = (o % tiles_n) * BN;
+    const int n_slices = K / 64;
+
+    uint32_t offA[2], offW[2];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int mb = m0 + wm * (BM / C::WM) + i * 32 + 4 * hi;
+    for (int j = 0; j < 2; ++j) {
+        const int r = (j * 4 + wave) * 8 + (lane >> 3);
+        offA[j] = (uint32_t)((int64_t)min(m0 + r, M - 1) * lda * 2 + (((lane & 7) ^ (r & 7)) * 16));
+        offW[j] = (uint32_t)((int64_t)min(n0 + r, N - 1) * ldw * 2 + (((lane & 7) ^ (r & 7)) * 16));
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    const unsigned char* gA = reinterpret_cast<const unsigned char*>(A);
+    const unsigned char* gW = reinterpret_cast<const unsigned char*>(W);
+    auto request = [&](int slice, int stage) __attribute__((always_inline)) {
+        const uint32_t sb = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            out_t* col = Cp + nn[j];
+        for (int j = 0; j < 2; ++j) lds_dma16(offA[j], gA + (int64_t)slice * 128, sb + j * 4096);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mb + 8 * (v >> 2) + (v & 3);
-                float zv = acc[i][j][v] + bv[j];
-                if (relu) zv = fmaxf(zv, 0.f);
-                if (sigm) zv = 1.0f / (1.0f + expf(-zv));
-                if (full || (m < M && nn[j] < N)) {
-                    if constexpr (C_BF16) col[(int64_t)m * ldc] = (uint16_t)pack_bf16(zv, 0.f);
-                    else col[(int64_t)m * ldc] = zv;
+        for (int j = 0; j < 2; ++j) lds_dma16(offW[j], gW + (int64_t)slice * 128, sb + BM * 128 + j * 4096);
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{0};
+    const int row = lane & 31, f = row & 7, hi = lane >> 5;
+    const int chunk = ((2 * wave + hi) ^ f) * 16;              // this wave's k chunk of every slice
+    bf16x8 af[2][2], wf[2][2];
+    auto load_frags = [&](int stage, int buf) __attribute__((always_inline)) {
+        const unsigned char* sa = lds + stage * STAGE_BYTES + row * 128 + chunk;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 4096);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(sa + BM * 128 + j * 4096);
+    };
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < n_slices) request(p, p);
+    wait_groups_barrier<LPT, NST - 2>(n_slices - 1);
+    load_frags(0, 0);
+    for (int t0 = 0; t0 < n_slices; t0 += NST) {
+#pragma unroll
+        for (int s = 0; s < NST; ++s) {
+            const int t = t0 + s;
+            if (t < n_slices) {
+                if (t + 1 < n_slices) {
+                    // slice t+1 has landed; every wave is past slice t-1, whose stage takes slice t+NST-1
+                    wait_groups_barrier<LPT, NST - 3>(n_slices - 2 - t);
+                    if (t + NST - 1 < n_slices) request(t + NST - 1, (s + NST - 1) % NST);
+                    load_frags((s + 1) % NST, (s + 1) & 1);
                 }
+                multiply(s & 1);
             }
         }
     }
+
+    // fold: partial tiles to LDS as [wave][register][lane], then wave w sums quarter w in wave order
+    wait_loads_lds_barrier<0>();                               // nobody still reads the ring
+    float* red = reinterpret_cast<float*>(lds);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[((wave * 4 + i * 2 + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+    __syncthreads();
+    floatx16 sum[1][1];
+    sum[0][0] = floatx16{0};
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum[0][0][v] += red[((w * 4 + wave) * 16 + v) * 64 + lane];
+    const int qi = wave >> 1, qj = wave & 1;
+    store_tiles<C_BF16, 1, 1>(sum, bias, Cv, ldc, M, N, m0 + qi * 32, n0 + qj * 32, (m0 + BM <= M) && (n0 + BN <= N), lane, act);
 }
 
 // fp32 rows -> bf16 rows (round to nearest even), 8 elements per thread; the first `scan_tiles`
@@ -260,21 +374,32 @@ __global__ __launch_bounds__(SCAN_THREADS) void prepare_bf16_kernel(const float*
     const int k8 = K / 8;
     const int64_t n8 = (int64_t)M * k8;
     const int64_t step = (int64_t)(gridDim.x - scan_tiles) * SCAN_THREADS;
-    for (int64_t i = (int64_t)(blockIdx.x - scan_tiles) * SCAN_THREADS + threadIdx.x; i < n8; i += step) {
-        const int64_t m = i / k8;
-        const int c = (int)(i - m * k8) * 8;
-        const float4 a = *reinterpret_cast<const float4*>(x + m * ldx + c);
-        const float4 b = *reinterpret_cast<const float4*>(x + m * ldx + c + 4);
-        const uint4 o = make_uint4(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w), pack_bf16(b.x, b.y), pack_bf16(b.z, b.w));
-        *reinterpret_cast<uint4*>(y + m * ldy + c) = o;
+    constexpr int U = 2;                                       // items per thread per round, loads first
+    for (int64_t i0 = (int64_t)(blockIdx.x - scan_tiles) * SCAN_THREADS + threadIdx.x; i0 < n8; i0 += U * step) {
+        float4 a[U], b[U];
+        int64_t dst[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * step;
+            const int64_t m = (i < n8 ? i : i0) / k8;
+            const int c = (int)((i < n8 ? i : i0) - m * k8) * 8;
+            a[u] = *reinterpret_cast<const float4*>(x + m * ldx + c);
+            b[u] = *reinterpret_cast<const float4*>(x + m * ldx + c + 4);
+            dst[u] = i < n8 ? m * ldy + c : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (dst[u] >= 0)
+                *reinterpret_cast<uint4*>(y + dst[u]) = make_uint4(pack_bf16(a[u].x, a[u].y), pack_bf16(a[u].z, a[u].w),
+                                                                   pack_bf16(b[u].x, b[u].y), pack_bf16(b[u].z, b[u].w));
     }
 }
 
-// Tile shapes, largest first; a shape is taken when it gives about a block per CU.
+// Tile shapes, largest first; a shape is taken when it gives about a block per CU.  Below these comes
+// the 64x64 tile of gemm_bf16_ks_kernel (8 stages of 16 KiB).
 typedef GemmCfg<256, 256, 4, 2, 2> Cfg256;      // 8 waves of 64x128, 2 stages of 64 KiB
 typedef GemmCfg<128, 128, 2, 2, 4> Cfg128;      // 4 waves of 64x64, 4 stages of 32 KiB
 typedef GemmCfg<128, 64, 2, 2, 5> Cfg128x64;    // 4 waves of 64x32, 5 stages of 24 KiB
-typedef GemmCfg<64, 64, 2, 2, 8> Cfg64;         // 4 waves of 32x32, 8 stages of 16 KiB
 
 constexpr int GEMM_MIN_BLOCKS = 200;      // about one block per CU
 
@@ -322,7 +447,7 @@ rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const v
     if (!x_bf16 || scan_tiles > 0) {
         // one preparing launch: bf16 copy of the activations, and the scan if one rides along
         const int64_t n8 = x_bf16 ? 0 : (int64_t)M * (K / 8);
-        int64_t blocks = (n8 + SCAN_THREADS - 1) / SCAN_THREADS;
+        int64_t blocks = (n8 + 2 * SCAN_THREADS - 1) / (2 * SCAN_THREADS);        // two items per thread
         blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
         hipLaunchKernelGGL(prepare_bf16_kernel, dim3((unsigned)(blocks + scan_tiles)), dim3(SCAN_THREADS), 0, s,
                            static_cast<const float*>(x), ldx, xh, (int64_t)K, x_bf16 ? 0 : M, K,
@@ -344,7 +469,12 @@ rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const v
     if (p.bm == 256) GEMM_GO(Cfg256);
     else if (p.bm == 128 && p.bn == 128) GEMM_GO(Cfg128);
     else if (p.bm == 128) GEMM_GO(Cfg128x64);
-    else GEMM_GO(Cfg64);
+    else if (y_bf16)
+        hipLaunchKernelGGL((gemm_bf16_ks_kernel<8, true>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K, bias, y,
+                           ldy, M, N, K, act);
+    else
+        hipLaunchKernelGGL((gemm_bf16_ks_kernel<8, false>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K, bias, y,
+                           ldy, M, N, K, act);
 #undef GEMM_GO
     REC_CHECK_LAUNCH();
     return REC_OK;
