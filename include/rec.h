@@ -99,6 +99,21 @@ rec_status rec_sls_forward_offsets(const float* const* tables, const int64_t* ro
                                    int32_t B, float* out, int64_t out_stride_b, int64_t out_stride_t,
                                    void* stream);
 
+/* rec_sls_forward for callers that cannot hand over or allocate scratch memory: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation calls.  Same
+ * arguments and result as rec_sls_forward minus the workspace: the bag offsets go to an array that
+ * is part of the library's device image (REC_SLS_STATIC_MAX_BAGS 64-bit offsets, 2 MiB, one copy
+ * per GPU the library runs on, held until the process ends).  Calls no allocation routine.
+ * Returns REC_ERR_WORKSPACE, and launches nothing, when T*B + 1 > REC_SLS_STATIC_MAX_BAGS.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on the same GPU (different
+ * streams or threads) race; calls on one stream do not.  Nothing needs clearing between calls (each
+ * call writes every offset before reading it). */
+#define REC_SLS_STATIC_MAX_BAGS 262144
+rec_status rec_sls_forward_static(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                                  const int32_t* indices, int64_t n_indices, const int32_t* lengths,
+                                  int32_t B, float* out, int64_t out_stride_b, int64_t out_stride_t,
+                                  void* stream);
+
 /* Exclusive prefix sum of bag lengths (the offsets used above):
  * offsets[0] = 0, offsets[i+1] = offsets[i] + lengths[i].
  * lengths DEV int32 [n_bags]; offsets DEV int64 [n_bags + 1], 16-byte aligned. */

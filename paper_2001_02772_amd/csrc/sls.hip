@@ -7,6 +7,8 @@
 // with about 80 (RMC1/2) or 20 (RMC3) lookups per table.  Sections III-A and
 // VI-A name this the memory-bound, irregular part, so the kernel is organised
 // around keeping many independent 16-byte row loads in flight per wavefront.
+#include <mutex>
+
 #include "rec_common.h"
 #include "scan_body.h"
 
@@ -308,6 +310,55 @@ rec_status rec_sls_forward(const float* const* tables, const int64_t* rows, int3
 }
 
 }  // extern "C"
+
+// ---- pooling without a workspace argument -------------------------------------------------------
+// The bag offsets of rec_sls_forward_static live in this array: one copy per GPU the library runs
+// on, held until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels get the device address that call returns.
+static __device__ __align__(256) unsigned char sls_static_scratch[REC_SLS_STATIC_MAX_BAGS * sizeof(int64_t) + 256];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex static_scratch_mutex;
+void* static_scratch_ptr[MAX_DEVICES];          // device address of the array on each device, once looked up
+
+// Device address of sls_static_scratch on the current device (looked up on the first call on that device).
+rec_status static_scratch(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return REC_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(static_scratch_mutex);
+    if (!static_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(sls_static_scratch)) != hipSuccess || !p) return REC_ERR_DEVICE;
+        static_scratch_ptr[dev] = p;
+    }
+    *ptr = static_scratch_ptr[dev];
+    return REC_OK;
+}
+}  // namespace
+
+extern "C" rec_status rec_sls_forward_static(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
+                                             const int32_t* indices, int64_t n_indices, const int32_t* lengths, int32_t B,
+                                             float* out, int64_t out_stride_b, int64_t out_stride_t, void* stream) {
+    rec_status st = check_sparse_args(rows, T, indices, n_indices, lengths, B);
+    if (st != REC_OK) return st;
+    if (!tables) return REC_ERR_NULL;
+    if (D < 4 || D > 256 || D % 4) return REC_ERR_UNSUPPORTED;
+    if ((int64_t)T * B + 1 > (int64_t)REC_SLS_STATIC_MAX_BAGS) return REC_ERR_WORKSPACE;   // more bags than the array holds
+    if (B == 0) return REC_OK;
+    if (!out) return REC_ERR_NULL;
+    if (out_stride_b < 0 || out_stride_t < 0 || out_stride_b % 4 || out_stride_t % 4 || !rec_aligned(out, 16))
+        return REC_ERR_BAD_SHAPE;
+    void* scratch = nullptr;
+    st = static_scratch(&scratch);
+    if (st != REC_OK) return st;
+    // every offset the pooling reads is written by the scan first, so nothing has to be cleared
+    int64_t* offsets = static_cast<int64_t*>(scratch);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = launch_offsets(lengths, (int64_t)T * B, offsets, s);
+    if (st != REC_OK) return st;
+    return rec_sls_launch(tables, T, D, indices, n_indices, offsets, B, out, out_stride_b, out_stride_t, s);
+}
 
 rec_status rec_sls_forward_step(const float* const* tables, const int64_t* rows, int32_t T, int32_t D,
                                 const int32_t* indices, int64_t n_indices, const int32_t* lengths, int32_t B, float* out,

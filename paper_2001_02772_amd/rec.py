@@ -27,7 +27,8 @@ INTERACT_DOT, INTERACT_CONCAT = 0, 1
 
 EXPORTS = (
     "rec_status_string", "rec_split_query",
-    "rec_sls_workspace_bytes", "rec_sls_forward", "rec_sls_forward_offsets", "rec_sls_offsets", "rec_sls_validate",
+    "rec_sls_workspace_bytes", "rec_sls_forward", "rec_sls_forward_static", "rec_sls_forward_offsets", "rec_sls_offsets",
+    "rec_sls_validate",
     "rec_mlp_workspace_bytes", "rec_mlp_forward", "rec_f32_to_bf16",
     "rec_interact",
     "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
@@ -78,6 +79,8 @@ def lib():
     L.rec_sls_workspace_bytes.argtypes = [i32, i32]
     L.rec_sls_forward.restype = C.c_int
     L.rec_sls_forward.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, i64, i64, vp, sz, vp]
+    L.rec_sls_forward_static.restype = C.c_int
+    L.rec_sls_forward_static.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, i64, i64, vp]
     L.rec_sls_forward_offsets.restype = C.c_int
     L.rec_sls_forward_offsets.argtypes = [vp, vp, i32, i32, vp, i64, vp, i32, vp, i64, i64, vp]
     L.rec_sls_offsets.restype = C.c_int
@@ -209,6 +212,21 @@ def sls_forward(tables: Tables, indices, lengths, B: int, out=None, out_stride_b
                                _ptr(lengths), B, _ptr(out), out_stride_b, out_stride_t, _ptr(workspace),
                                workspace.numel(), _stream())
     _check(st, "rec_sls_forward")
+    return out
+
+
+SLS_STATIC_MAX_BAGS = 262144
+
+
+def sls_forward_static(tables: Tables, indices, lengths, B: int, out=None, out_stride_b=None, out_stride_t=None):
+    """rec_sls_forward_static: the same pooling with the offsets in the library's own static device array."""
+    T, D = tables.T, tables.D
+    if out is None:
+        out = torch.empty((B, T, D), dtype=torch.float32, device=tables.ptrs.device)
+        out_stride_b, out_stride_t = T * D, D
+    st = lib().rec_sls_forward_static(_ptr(tables.ptrs), tables.rows.ctypes.data, T, D, _ptr(indices), indices.numel(),
+                                      _ptr(lengths), B, _ptr(out), out_stride_b, out_stride_t, _stream())
+    _check(st, "rec_sls_forward_static")
     return out
 
 
