@@ -332,6 +332,10 @@ rec_status launch_layer(const void* x, bool x_bf16, int64_t ldx, const void* W, 
                         void* gemm_area, const rec_scan_job* scan, hipStream_t s) {
     if (layer_takes_gemm(x, x_bf16, ldx, W, dt, B, n_in, n_out))
         return rec_gemm_bf16_launch(x, x_bf16, ldx, W, bias, y, y_bf16, ldy, gemm_area, B, n_out, n_in, act, scan, s);
+    if (dt == REC_F32 && rec_gemm_f32_plan(B, n_out, n_in).tiles != 0 && rec_aligned(x, 16) && rec_aligned(W, 16) &&
+        ldx % 4 == 0 && (int64_t)B * ldx * 4 < ((int64_t)1 << 32))
+        return rec_gemm_f32_launch(static_cast<const float*>(x), ldx, static_cast<const float*>(W), bias, static_cast<float*>(y),
+                                   ldy, B, n_out, n_in, act, s);
     int shape, ksplit;
     choose_shape(B, n_out, n_in, dt == REC_BF16, &shape, &ksplit);
     if (dt == REC_F32) {

@@ -261,18 +261,24 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(const uint16_t* _
                                 (m0 + BM <= M) && (n0 + BN <= N), lane, act);
 }
 
-// The smallest tile, 64x64, with the four waves splitting k instead of the tile: wave w multiplies the
-// whole tile (2x2 MFMA tiles) for k chunk w of every 64-wide slice, so a slice costs 16 KiB of fragment
-// reads instead of 32 (with the 16 KiB the loads write, LDS traffic per slice drops by a third, and at
-// this tile size LDS is what the matrix cores wait for).  The four partial tiles meet in LDS at the end
-// and are added in wave order, each wave finishing one 32x32 quarter.  Same requirements as above.
-template <int NST, bool C_BF16>
-__global__ __launch_bounds__(256) void gemm_bf16_ks_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                          const uint16_t* __restrict__ W, int64_t ldw,
-                                                          const float* __restrict__ bias, void* __restrict__ Cv, int64_t ldc,
-                                                          int M, int N, int K, int act) {
-    constexpr int BM = 64, BN = 64, STAGE_BYTES = (BM + BN) * 128, LPT = 4;
-    static_assert(NST % 2 == 0 && NST >= 4 && NST * STAGE_BYTES >= 4 * 64 * 64 * 4, "ring doubles as the fold buffer");
+// Small tiles (64x64 or 64x32) with the four waves splitting k instead of the tile: wave w multiplies
+// the whole tile for the w-th quarter of every 128-byte k slice, so a slice of a 64x64 tile costs 16 KiB
+// of fragment reads instead of 32 (with the 16 KiB the loads write, LDS traffic per slice drops by a
+// third, and at this tile size LDS is what the bf16 matrix cores wait for).  The four partial tiles meet
+// in LDS at the end and are added in wave order, one 32x32 MFMA tile per wave.
+// F32: operands are fp32 (a slice is 32 k wide) and go through v_mfma_f32_32x32x2_f32: a lane's 16-byte
+// fragment holds 4 consecutive k, component e of the two lane halves feeds MFMA e -- activations and
+// weights use the same assignment, so every k is multiplied exactly once.  The fp32 matrix rate is a
+// sixteenth of the bf16 one, which makes such a layer compute-bound and the tile as small as it takes
+// to give every CU a block.  Requirements as for gemm_bf16_kernel, with K % 32 == 0 for fp32.
+template <int TM, int TN, int NST, bool F32, bool C_BF16>
+__global__ __launch_bounds__(256) void gemm_ks_kernel(const void* __restrict__ A, int64_t lda, const void* __restrict__ W,
+                                                     int64_t ldw, const float* __restrict__ bias, void* __restrict__ Cv,
+                                                     int64_t ldc, int M, int N, int K, int act) {
+    constexpr int BM = 32 * TM, BN = 32 * TN, STAGE_BYTES = (BM + BN) * 128, LPT = TM + TN;
+    constexpr int ELT = F32 ? 4 : 2, KS = 128 / ELT;           // bytes per element, k per slice
+    static_assert(NST % 2 == 0 && NST >= 4 && NST * STAGE_BYTES >= 4 * TM * TN * 16 * 64 * 4, "ring doubles as the fold buffer");
+    static_assert(NST * STAGE_BYTES <= 160 * 1024 && (NST - 1) * LPT < 64 && TM * TN <= 4, "LDS, vmcnt, one tile per wave in the fold");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -283,47 +289,60 @@ __global__ __launch_bounds__(256) void gemm_bf16_ks_kernel(const uint16_t* __res
     }
     const int tiles_n = (N + BN - 1) / BN;
     const int m0 = (o / tiles_n) * BM, n0 = (o % tiles_n) * BN;
-    const int n_slices = K / 64;
+    const int n_slices = K / KS;
 
-    uint32_t offA[2], offW[2];
+    uint32_t offA[TM], offW[TN];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < TM; ++j) {
         const int r = (j * 4 + wave) * 8 + (lane >> 3);
-        offA[j] = (uint32_t)((int64_t)min(m0 + r, M - 1) * lda * 2 + (((lane & 7) ^ swz(r)) * 16));
-        offW[j] = (uint32_t)((int64_t)min(n0 + r, N - 1) * ldw * 2 + (((lane & 7) ^ swz(r)) * 16));
+        offA[j] = (uint32_t)((int64_t)min(m0 + r, M - 1) * lda * ELT + (((lane & 7) ^ swz(r)) * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int r = (j * 4 + wave) * 8 + (lane >> 3);
+        offW[j] = (uint32_t)((int64_t)min(n0 + r, N - 1) * ldw * ELT + (((lane & 7) ^ swz(r)) * 16));
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-    const unsigned char* gA = reinterpret_cast<const unsigned char*>(A);
-    const unsigned char* gW = reinterpret_cast<const unsigned char*>(W);
+    const unsigned char* gA = static_cast<const unsigned char*>(A);
+    const unsigned char* gW = static_cast<const unsigned char*>(W);
     auto request = [&](int slice, int stage) __attribute__((always_inline)) {
         const uint32_t sb = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) lds_dma16(offA[j], gA + (int64_t)slice * 128, sb + j * 4096);
+        for (int j = 0; j < TM; ++j) lds_dma16(offA[j], gA + (int64_t)slice * 128, sb + j * 4096);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) lds_dma16(offW[j], gW + (int64_t)slice * 128, sb + BM * 128 + j * 4096);
+        for (int j = 0; j < TN; ++j) lds_dma16(offW[j], gW + (int64_t)slice * 128, sb + BM * 128 + j * 4096);
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{0};
-    const int row = lane & 31, f = swz(row), hi = lane >> 5;
-    const int chunk = ((2 * wave + hi) ^ f) * 16;              // this wave's k chunk of every slice
-    bf16x8 af[2][2], wf[2][2];
+        for (int j = 0; j < TN; ++j) acc[i][j] = floatx16{0};
+    const int row = lane & 31, hi = lane >> 5;
+    const int chunk = ((2 * wave + hi) ^ swz(row)) * 16;       // this wave's quarter of every slice
+    float4 af[2][TM], wf[2][TN];                                // 16-byte fragments (8 bf16 or 4 fp32)
     auto load_frags = [&](int stage, int buf) __attribute__((always_inline)) {
         const unsigned char* sa = lds + stage * STAGE_BYTES + row * 128 + chunk;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 4096);
+        for (int i = 0; i < TM; ++i) af[buf][i] = *reinterpret_cast<const float4*>(sa + i * 4096);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(sa + BM * 128 + j * 4096);
+        for (int j = 0; j < TN; ++j) wf[buf][j] = *reinterpret_cast<const float4*>(sa + BM * 128 + j * 4096);
     };
     auto multiply = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], wf[buf][j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (F32) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[buf][i].x, wf[buf][j].x, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[buf][i].y, wf[buf][j].y, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[buf][i].z, wf[buf][j].z, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[buf][i].w, wf[buf][j].w, acc[i][j], 0, 0, 0);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[buf][i]),
+                                                                        __builtin_bit_cast(bf16x8, wf[buf][j]), acc[i][j], 0, 0, 0);
+                }
+            }
     };
 
 #pragma unroll
@@ -347,23 +366,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_ks_kernel(const uint16_t* __res
         }
     }
 
-    // fold: partial tiles to LDS as [wave][register][lane], then wave w sums quarter w in wave order
+    // fold: partial tiles to LDS as [wave][register][lane], then wave q sums MFMA tile q in wave order
     wait_loads_lds_barrier<0>();                               // nobody still reads the ring
     float* red = reinterpret_cast<float*>(lds);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[((wave * 4 + i * 2 + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+            for (int v = 0; v < 16; ++v) red[((wave * (TM * TN) + i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
     __syncthreads();
+    if (wave >= TM * TN) return;
     floatx16 sum[1][1];
     sum[0][0] = floatx16{0};
 #pragma unroll
     for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sum[0][0][v] += red[((w * 4 + wave) * 16 + v) * 64 + lane];
-    const int qi = wave >> 1, qj = wave & 1;
+        for (int v = 0; v < 16; ++v) sum[0][0][v] += red[((w * (TM * TN) + wave) * 16 + v) * 64 + lane];
+    const int qi = wave / TN, qj = wave % TN;
     store_tiles<C_BF16, 1, 1>(sum, bias, Cv, ldc, M, N, m0 + qi * 32, n0 + qj * 32, (m0 + BM <= M) && (n0 + BN <= N), lane, act);
 }
 
@@ -403,7 +423,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void prepare_bf16_kernel(const float*
 }
 
 // Tile shapes, largest first; a shape is taken when it gives about a block per CU.  Below these comes
-// the 64x64 tile of gemm_bf16_ks_kernel (8 stages of 16 KiB).
+// the 64x64 tile of gemm_ks_kernel (8 stages of 16 KiB).
 typedef GemmCfg<256, 256, 4, 2, 2> Cfg256;      // 8 waves of 64x128, 2 stages of 64 KiB
 typedef GemmCfg<128, 128, 2, 2, 4> Cfg128;      // 4 waves of 64x64, 4 stages of 32 KiB
 typedef GemmCfg<128, 64, 2, 2, 5> Cfg128x64;    // 4 waves of 64x32, 5 stages of 24 KiB
@@ -477,12 +497,40 @@ rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const v
     else if (p.bm == 128 && p.bn == 128) GEMM_GO(Cfg128);
     else if (p.bm == 128) GEMM_GO(Cfg128x64);
     else if (y_bf16)
-        hipLaunchKernelGGL((gemm_bf16_ks_kernel<8, true>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K, bias, y,
-                           ldy, M, N, K, act);
+        hipLaunchKernelGGL((gemm_ks_kernel<2, 2, 8, false, true>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K,
+                           bias, y, ldy, M, N, K, act);
     else
-        hipLaunchKernelGGL((gemm_bf16_ks_kernel<8, false>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K, bias, y,
-                           ldy, M, N, K, act);
+        hipLaunchKernelGGL((gemm_ks_kernel<2, 2, 8, false, false>), dim3((unsigned)p.tiles), dim3(256), 0, s, Ab, lda, Wb, (int64_t)K,
+                           bias, y, ldy, M, N, K, act);
 #undef GEMM_GO
+    REC_CHECK_LAUNCH();
+    return REC_OK;
+}
+
+// ---- fp32 layers on the same machinery -------------------------------------------------------------
+rec_gemm_plan rec_gemm_f32_plan(int M, int N, int K) {
+    rec_gemm_plan p = {0, 0, 0};
+    if (M < 1 || N < 1 || K < 256 || K % 32 != 0) return p;
+    if ((int64_t)M * K * 4 >= (int64_t)1 << 32 || (int64_t)N * K * 4 >= (int64_t)1 << 32) return p;
+    const int64_t t64 = tile_count(M, N, 64, 64), t6432 = tile_count(M, N, 64, 32);
+    if (t64 >= GEMM_MIN_BLOCKS) {
+        p.bm = 64, p.bn = 64, p.tiles = (int)t64;
+    } else if (t6432 >= 128) {
+        p.bm = 64, p.bn = 32, p.tiles = (int)t6432;
+    }
+    return p;
+}
+
+rec_status rec_gemm_f32_launch(const float* x, int64_t ldx, const float* W, const float* bias, float* y, int64_t ldy, int M,
+                               int N, int K, int act, hipStream_t s) {
+    const rec_gemm_plan p = rec_gemm_f32_plan(M, N, K);
+    if (p.tiles == 0) return REC_ERR_UNSUPPORTED;
+    if (p.bn == 64)
+        hipLaunchKernelGGL((gemm_ks_kernel<2, 2, 8, true, false>), dim3((unsigned)p.tiles), dim3(256), 0, s, x, ldx, W, (int64_t)K, bias,
+                           y, ldy, M, N, K, act);
+    else
+        hipLaunchKernelGGL((gemm_ks_kernel<2, 1, 8, true, false>), dim3((unsigned)p.tiles), dim3(256), 0, s, x, ldx, W, (int64_t)K, bias,
+                           y, ldy, M, N, K, act);
     REC_CHECK_LAUNCH();
     return REC_OK;
 }

@@ -162,7 +162,10 @@ rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     m->concat = concat;
     m->top_widths_run = m->top_widths;
     const int32_t k0 = d->top_widths[0];
-    const int32_t align = (d->mlp_dtype == REC_BF16) ? 8 : 4;       // elements per 16-byte load
+    int32_t align = (d->mlp_dtype == REC_BF16) ? 8 : 4;             // elements per 16-byte load
+    // a wide first predictor layer runs on the tiled matrix kernels when its k is a multiple of their
+    // 128-byte slice (884 -> 896 for 40 tables of width 64)
+    if (k0 >= 256) align *= 8;
     m->top_k0 = k0;
     if (!concat && k0 % align != 0) {
         const int32_t kp = (k0 + align - 1) / align * align;

@@ -121,3 +121,7 @@ size_t rec_gemm_bf16_workspace_bytes(int M, int N, int K, bool x_bf16);
 rec_status rec_gemm_bf16_launch(const void* x, bool x_bf16, int64_t ldx, const void* W, const float* bias, void* y,
                                 bool y_bf16, int64_t ldy, void* workspace, int M, int N, int K, int act,
                                 const rec_scan_job* scan, hipStream_t s);
+// The same for fp32 layers (K a multiple of 32, x and W 16-byte aligned, ldx a multiple of 4).
+rec_gemm_plan rec_gemm_f32_plan(int M, int N, int K);
+rec_status rec_gemm_f32_launch(const float* x, int64_t ldx, const float* W, const float* bias, float* y, int64_t ldy, int M,
+                               int N, int K, int act, hipStream_t s);

@@ -189,7 +189,8 @@ def test_interact_vs_oracle(rec, V, D, B):
                                       ((884, 512, 128, 1), 1024), ((5, 1), 1), ((70, 33, 65, 2), 63),
                                       ((20, 24, 28, 32, 36, 40, 3), 50), ((64, 32, 1000, 16), 40),
                                       ((512, 512, 7), 17), ((600, 64, 700, 5), 33),
-                                      ((320, 8), 33), ((448, 40, 17), 20), ((192, 100), 16), ((384, 24), 5)])
+                                      ((320, 8), 33), ((448, 40, 17), 20), ((192, 100), 16), ((384, 24), 5),
+                                      ((896, 512), 1024), ((512, 700), 900), ((256, 1024, 8), 1500), ((288, 130), 2100)])
 def test_mlp_f32_vs_oracle(rec, widths, B):
     p = synth.mlp_params(widths, stack=3)
     x = rng.uniform(0, 1, size=(B, widths[0])).astype(np.float32)
