@@ -177,9 +177,17 @@ rec_status rec_interact(const float* vecs, int32_t B, int32_t V, int32_t D,
  * E_t = pooled embedding of table t.  x's width must be a multiple of 4.
  * The handle BORROWS every pointer in the descriptor: DEV memory must stay
  * alive and unchanged while the handle is used; HOST arrays are copied.
- * rec_model_create may allocate device memory of its own (a copy of the first top
- * layer's weights with rows padded to a multiple of 16 bytes when the interaction
- * width is not one; synchronises the device once); rec_model_destroy frees it. */
+ *
+ * Padded weights.  The dot interaction's width D + T(T+1)/2 is rarely a multiple of what
+ * the FC kernels load at a time, so the model runs the first top layer on a copy of its
+ * weights with zero-padded rows (rec_model_padded_weight_bytes() says how large; 0 = none
+ * needed).  Two ways to provide it:
+ *   - desc.padded_weights = NULL: rec_model_create allocates the copy, fills it and
+ *     synchronises the device once; rec_model_destroy frees it.
+ *   - desc.padded_weights = a DEV buffer of at least that many bytes, 256-byte aligned,
+ *     owned by the caller: rec_model_create is then host-only (no device allocation, no
+ *     device work, no synchronisation) and the caller enqueues rec_model_prepare() once
+ *     before the first forward. */
 typedef enum { REC_INTERACT_DOT = 0, REC_INTERACT_CONCAT = 1 } rec_interaction;
 
 typedef struct {
@@ -198,15 +206,25 @@ typedef struct {
     rec_dtype mlp_dtype;             /* REC_F32 or REC_BF16, both stacks */
     rec_interaction interaction;     /* REC_INTERACT_DOT: bottom_widths last = D, top_widths[0] = D + T(T+1)/2;
                                         REC_INTERACT_CONCAT: top_widths[0] = bottom_widths last + T*D */
+    void* padded_weights;            /* DEV, caller-owned, or NULL (see "Padded weights" above) */
+    size_t padded_weights_bytes;     /* size of that buffer */
 } rec_model_desc;
 
 typedef struct rec_model rec_model;
 
+/* Bytes of the padded copy of the first top layer's weights this descriptor needs (0: none).
+ * HOST only; looks at the widths and dtype, not at the pointers. */
+size_t rec_model_padded_weight_bytes(const rec_model_desc* desc);
 rec_status rec_model_create(const rec_model_desc* desc, rec_model** out);
+/* Fills the caller-provided padded-weights buffer (one small launch on `stream`, no allocation,
+ * no synchronisation).  Needed once, before the first forward, only when desc.padded_weights was
+ * given and rec_model_padded_weight_bytes() > 0; otherwise a no-op.  Until then the forward
+ * calls return REC_ERR_BAD_SHAPE.  Call it from one thread, before the handle is shared. */
+rec_status rec_model_prepare(rec_model* m, void* stream);
 void rec_model_destroy(rec_model* m);
 size_t rec_model_workspace_bytes(const rec_model* m, int32_t B_max);
 
-/*   dense    DEV fp32 [B][F] contiguous
+/*   dense    DEV fp32 [B][F] contiguous (16-byte aligned when the model has no bottom stack)
  *   indices  DEV int32 [n_indices];  lengths DEV int32 [T*B]
  *   prob     DEV fp32 [B]
  *   workspace >= rec_model_workspace_bytes(m, B) */

@@ -22,6 +22,9 @@ struct rec_model {
     // element-wise loads.  The model then owns a copy of that layer's weights with every row
     // zero-padded to `top_k0` columns, and the interaction writes zeros into the matching columns.
     void* top_W0_padded = nullptr;
+    bool owns_padded = false;              // allocated by rec_model_create (else the caller's buffer)
+    bool prepared = true;                  // the padded copy holds the weights (false until rec_model_prepare)
+    const void* top_W0_src = nullptr;      // the caller's unpadded weights of that layer
     std::vector<int32_t> top_widths_run;   // top_widths with [0] = top_k0
     int32_t top_k0;
     int64_t ld_inter;        // row stride of the interaction output (dot) or of the joined row (concat)
@@ -78,6 +81,26 @@ __global__ __launch_bounds__(SCAN_THREADS) void copy_rows_scan_kernel(const floa
         const int32_t c = (int32_t)(i - b * (F / 4)) * 4;
         *reinterpret_cast<float4*>(dst + b * ld_dst + c) = *reinterpret_cast<const float4*>(src + b * F + c);
     }
+}
+
+// dst[r][0..kp) = src[r][0..k) followed by zeros, rows of `elt`-byte elements.
+__global__ __launch_bounds__(256) void pad_rows_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst,
+                                                       int64_t rows, int32_t k, int32_t kp, int32_t elt) {
+    const int64_t n = rows * kp;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / kp;
+        const int32_t c = (int32_t)(i - r * kp);
+        for (int32_t b = 0; b < elt; ++b) dst[i * elt + b] = c < k ? src[(r * k + c) * elt + b] : (unsigned char)0;
+    }
+}
+
+// Columns the first predictor layer's k is padded to (k itself when no padding is needed).
+int32_t padded_k0(int32_t k0, rec_dtype dt, bool concat) {
+    int32_t align = (dt == REC_BF16) ? 8 : 4;                       // elements per 16-byte load
+    // a wide first predictor layer runs on the tiled matrix kernels when its k is a multiple of their
+    // 128-byte slice (884 -> 896 for 40 tables of width 64)
+    if (k0 >= 256) align *= 8;
+    return (!concat && k0 % align != 0) ? (k0 + align - 1) / align * align : k0;
 }
 
 }  // namespace
@@ -162,40 +185,72 @@ rec_status rec_model_create(const rec_model_desc* d, rec_model** out) {
     m->concat = concat;
     m->top_widths_run = m->top_widths;
     const int32_t k0 = d->top_widths[0];
-    int32_t align = (d->mlp_dtype == REC_BF16) ? 8 : 4;             // elements per 16-byte load
-    // a wide first predictor layer runs on the tiled matrix kernels when its k is a multiple of their
-    // 128-byte slice (884 -> 896 for 40 tables of width 64)
-    if (k0 >= 256) align *= 8;
-    m->top_k0 = k0;
-    if (!concat && k0 % align != 0) {
-        const int32_t kp = (k0 + align - 1) / align * align;
-        const size_t elt = (d->mlp_dtype == REC_BF16) ? 2 : 4;
-        const size_t n_out = (size_t)d->top_widths[1];
-        void* padded = nullptr;
-        if (hipMalloc(&padded, n_out * kp * elt) != hipSuccess) {
-            delete m;
-            return REC_ERR_DEVICE;
-        }
-        if (hipMemset(padded, 0, n_out * kp * elt) != hipSuccess ||
-            hipMemcpy2D(padded, kp * elt, d->top_W[0], k0 * elt, k0 * elt, n_out, hipMemcpyDeviceToDevice) != hipSuccess ||
-            hipDeviceSynchronize() != hipSuccess) {
-            (void)hipFree(padded);
-            delete m;
-            return REC_ERR_DEVICE;
-        }
-        m->top_W0_padded = padded;
-        m->top_W[0] = padded;
+    const int32_t kp = padded_k0(k0, d->mlp_dtype, concat);
+    m->top_k0 = kp;
+    if (kp != k0) {
+        const size_t need = rec_model_padded_weight_bytes(d);
+        m->top_W0_src = d->top_W[0];
         m->top_widths_run[0] = kp;
-        m->top_k0 = kp;
+        if (d->padded_weights) {
+            // the caller's buffer: nothing touches the device here; rec_model_prepare fills it
+            if (d->padded_weights_bytes < need || !rec_aligned(d->padded_weights, 256)) {
+                delete m;
+                return REC_ERR_WORKSPACE;
+            }
+            m->top_W0_padded = d->padded_weights;
+            m->prepared = false;
+        } else {
+            const size_t elt = (d->mlp_dtype == REC_BF16) ? 2 : 4;
+            const size_t n_out = (size_t)d->top_widths[1];
+            void* padded = nullptr;
+            if (hipMalloc(&padded, need) != hipSuccess) {
+                delete m;
+                return REC_ERR_DEVICE;
+            }
+            if (hipMemset(padded, 0, need) != hipSuccess ||
+                hipMemcpy2D(padded, kp * elt, d->top_W[0], k0 * elt, k0 * elt, n_out, hipMemcpyDeviceToDevice) != hipSuccess ||
+                hipDeviceSynchronize() != hipSuccess) {
+                (void)hipFree(padded);
+                delete m;
+                return REC_ERR_DEVICE;
+            }
+            m->top_W0_padded = padded;
+            m->owns_padded = true;
+        }
+        m->top_W[0] = m->top_W0_padded;
     }
     m->ld_inter = (m->top_k0 + 3) / 4 * 4;
     *out = m;
     return REC_OK;
 }
 
+size_t rec_model_padded_weight_bytes(const rec_model_desc* d) {
+    if (!d || !d->top_widths || d->n_top < 1) return 0;
+    if (d->mlp_dtype != REC_F32 && d->mlp_dtype != REC_BF16) return 0;
+    const int32_t k0 = d->top_widths[0];
+    if (k0 < 1 || d->top_widths[1] < 1) return 0;
+    const int32_t kp = padded_k0(k0, d->mlp_dtype, d->interaction == REC_INTERACT_CONCAT);
+    if (kp == k0) return 0;
+    return rec_round_up((size_t)d->top_widths[1] * kp * (d->mlp_dtype == REC_BF16 ? 2 : 4), 256);
+}
+
+rec_status rec_model_prepare(rec_model* m, void* stream) {
+    if (!m) return REC_ERR_NULL;
+    if (m->prepared) return REC_OK;
+    const int32_t k0 = m->top_widths[0], kp = m->top_k0, elt = (m->dt == REC_BF16) ? 2 : 4;
+    const int64_t rows = m->top_widths[1];
+    const int64_t n = rows * kp;
+    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 1024)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const unsigned char*>(m->top_W0_src),
+                       static_cast<unsigned char*>(m->top_W0_padded), rows, k0, kp, elt);
+    REC_CHECK_LAUNCH();
+    m->prepared = true;
+    return REC_OK;
+}
+
 void rec_model_destroy(rec_model* m) {
     if (!m) return;
-    if (m->top_W0_padded) (void)hipFree(m->top_W0_padded);
+    if (m->top_W0_padded && m->owns_padded) (void)hipFree(m->top_W0_padded);
     delete m;
 }
 
@@ -209,6 +264,7 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
                              size_t workspace_bytes, void* stream) {
     if (!m) return REC_ERR_NULL;
     if (B < 0 || n_indices < 0) return REC_ERR_BAD_SHAPE;
+    if (!m->prepared) return REC_ERR_BAD_SHAPE;                     // rec_model_prepare has not run
     if (B == 0) return REC_OK;
     if (!dense || !lengths || !prob || (n_indices > 0 && !indices)) return REC_ERR_NULL;
     if (!workspace || !rec_aligned(workspace, 256)) return REC_ERR_WORKSPACE;
@@ -223,6 +279,7 @@ rec_status rec_model_forward(const rec_model* m, const float* dense, const int32
         const int32_t X = m->bottom_widths.back();
         const int64_t ldc = m->ld_inter;
         if (m->bottom_W.empty()) {
+            if (!rec_aligned(dense, 16)) return REC_ERR_BAD_SHAPE;  // the row copy below loads 16 bytes at a time
             rec_status st = rec_sls_forward_step(m->tables, m->rows.data(), m->T, D, indices, n_indices, lengths, B,
                                                  w.inter + X, ldc, D, w.sls, w.sls_bytes, stream, REC_SLS_CHECK_ONLY);
             if (st != REC_OK) return st;

@@ -31,7 +31,8 @@ EXPORTS = (
     "rec_sls_validate",
     "rec_mlp_workspace_bytes", "rec_mlp_forward", "rec_f32_to_bf16",
     "rec_interact",
-    "rec_model_create", "rec_model_destroy", "rec_model_workspace_bytes", "rec_model_forward",
+    "rec_model_padded_weight_bytes", "rec_model_create", "rec_model_prepare", "rec_model_destroy", "rec_model_workspace_bytes",
+    "rec_model_forward",
     "rec_sched_query_service", "rec_sched_fifo_latencies", "rec_sched_percentile", "rec_sched_max_qps",
     "rec_sched_hill_climb", "rec_sched_two_tier_latencies", "rec_sched_two_tier_max_qps", "rec_serve_trace", "rec_serve_trace_many", "rec_model_forward_many",
     "rec_stream_pool_create", "rec_stream_pool_destroy", "rec_stream_pool_size", "rec_stream_pool_stream",
@@ -97,6 +98,10 @@ def lib():
     L.rec_interact.argtypes = [vp, i32, i32, i32, vp, i64, vp]
     L.rec_model_create.restype = C.c_int
     L.rec_model_create.argtypes = [vp, vp]
+    L.rec_model_padded_weight_bytes.restype = sz
+    L.rec_model_padded_weight_bytes.argtypes = [vp]
+    L.rec_model_prepare.restype = C.c_int
+    L.rec_model_prepare.argtypes = [vp, vp]
     L.rec_model_destroy.restype = None
     L.rec_model_destroy.argtypes = [vp]
     L.rec_model_workspace_bytes.restype = sz
@@ -306,15 +311,18 @@ class _ModelDesc(C.Structure):
                 ("n_bottom", C.c_int32), ("bottom_widths", C.c_void_p), ("bottom_W", C.c_void_p),
                 ("bottom_b", C.c_void_p),
                 ("n_top", C.c_int32), ("top_widths", C.c_void_p), ("top_W", C.c_void_p), ("top_b", C.c_void_p),
-                ("mlp_dtype", C.c_int), ("interaction", C.c_int)]
+                ("mlp_dtype", C.c_int), ("interaction", C.c_int),
+                ("padded_weights", C.c_void_p), ("padded_weights_bytes", C.c_size_t)]
 
 
 class Model:
     """Owns the device tensors of one model and the library handle that borrows them."""
 
     def __init__(self, tables: Tables, bottom_W, bottom_b, top_W, top_b, wdtype=F32, interaction=INTERACT_DOT,
-                 dense_features: int | None = None):
-        """interaction=INTERACT_CONCAT allows an empty bottom stack; then pass dense_features = F."""
+                 dense_features: int | None = None, caller_padded_weights: bool = False):
+        """interaction=INTERACT_CONCAT allows an empty bottom stack; then pass dense_features = F.
+        caller_padded_weights: hand the library a buffer for its padded weight copy (host-only create
+        + rec_model_prepare) instead of letting rec_model_create allocate it."""
         self.tables, self.wdtype, self.interaction = tables, wdtype, interaction
         self.bottom_W, self.bottom_b, self.top_W, self.top_b = list(bottom_W), list(bottom_b), list(top_W), list(top_b)
         self.bottom_widths = _host_i32([bottom_W[0].shape[1] if self.bottom_W else dense_features]
@@ -325,11 +333,18 @@ class Model:
         d = _ModelDesc(tables.T, tables.D, _ptr(tables.ptrs), tables.rows.ctypes.data,
                        len(self.bottom_W), self.bottom_widths.ctypes.data, C.addressof(arrays[0]), C.addressof(arrays[1]),
                        len(self.top_W), self.top_widths.ctypes.data, C.addressof(arrays[2]), C.addressof(arrays[3]),
-                       wdtype, interaction)
+                       wdtype, interaction, None, 0)
+        self.padded_weight_bytes = lib().rec_model_padded_weight_bytes(C.addressof(d))
+        self._padded = None
+        if caller_padded_weights and self.padded_weight_bytes:
+            self._padded = _workspace(self.padded_weight_bytes, self.device)
+            d.padded_weights, d.padded_weights_bytes = _ptr(self._padded), self._padded.numel()
         h = C.c_void_p(0)
         _check(lib().rec_model_create(C.addressof(d), C.addressof(h)), "rec_model_create")
         self._h = h
         self._ws = None
+        if self._padded is not None:
+            _check(lib().rec_model_prepare(self._h, _stream()), "rec_model_prepare")
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

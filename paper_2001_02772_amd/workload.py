@@ -21,13 +21,14 @@ def device_mlp(params: synth.MLPParams, bf16: bool, device="cuda"):
     return W, b
 
 
-def device_model(cfg: synth.Config, device="cuda", seed: int = synth.MASTER_SEED, tables: rec.Tables | None = None):
+def device_model(cfg: synth.Config, device="cuda", seed: int = synth.MASTER_SEED, tables: rec.Tables | None = None,
+                 caller_padded_weights: bool = False):
     tables = tables if tables is not None else device_tables(cfg, device, seed)
     Wb, bb = device_mlp(synth.mlp_params(cfg.bottom, 0, seed), cfg.bf16, device)
     Wt, bt = device_mlp(synth.mlp_params(cfg.top, 1, seed), cfg.bf16, device)
     return rec.Model(tables, Wb, bb, Wt, bt, rec.BF16 if cfg.bf16 else rec.F32,
                      interaction=rec.INTERACT_CONCAT if cfg.interaction == "concat" else rec.INTERACT_DOT,
-                     dense_features=cfg.F)
+                     dense_features=cfg.F, caller_padded_weights=caller_padded_weights)
 
 
 class DeviceBatch:

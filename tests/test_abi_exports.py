@@ -73,3 +73,55 @@ def test_serving_entry_points_reject_bad_arguments_on_the_host(rec):
     assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 0, 1, None) == rec.ERR_BAD_SHAPE
     assert L.rec_serve_trace_many(None, None, None, None, 2, None, None, 0, None, 1, 1, None) == rec.ERR_NULL
     assert L.rec_serve_trace(None, None, None, None, -1, None, None, 0, None, None) == rec.ERR_BAD_SHAPE
+
+
+def test_header_is_c99_and_host_entry_points_work_from_c(rec, tmp_path):
+    """tests/c_abi_host.c includes include/rec.h as C99 and calls the host-side entry points."""
+    import subprocess
+    exe = str(tmp_path / "c_abi_host")
+    libdir = os.path.dirname(rec.LIB_PATH)
+    cc = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I" + os.path.join(ROOT, "include"),
+          os.path.join(ROOT, "tests", "c_abi_host.c"), "-o", exe, "-L" + libdir, "-l:librec.so", "-lm",
+          "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
+    r = subprocess.run(cc, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "c abi ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_mlp_workspace_never_shrinks_with_the_batch(rec):
+    """A workspace sized for the largest batch serves every smaller one (the serving entry points rely on it)."""
+    for widths, dt in (([2560, 1024, 256, 32], rec.BF16), ([87, 512, 256, 1], rec.BF16), ([2048, 1024, 512, 256, 1], rec.BF16),
+                       ([884, 512, 128, 1], rec.F32), ([896, 512, 128, 1], rec.F32)):
+        top = rec.mlp_workspace_bytes(widths, 4096, dt)
+        prev = 0
+        for B in list(range(1, 300)) + list(range(300, 4097, 7)) + [4096]:
+            b = rec.mlp_workspace_bytes(widths, B, dt)
+            assert prev <= b <= top, (widths, B, prev, b, top)
+            prev = b
+
+
+def test_host_only_model_create_with_a_caller_buffer(rec):
+    """With a caller-provided padded-weights buffer rec_model_create touches no device (it works here, without
+    one), and the forward refuses to run until rec_model_prepare has filled the buffer."""
+    import ctypes as C
+    import numpy as np
+    L = rec.lib()
+    fake = 0x7f0000001000                                   # never dereferenced on the host; 256-byte aligned
+    bw, tw = np.array([13, 32], np.int32), np.array([87, 64, 1], np.int32)
+    rows = np.full(10, 1000, np.int64)
+    ptrs = (C.c_void_p * 2)(fake, fake)
+    d = rec._ModelDesc(10, 32, fake, rows.ctypes.data, 1, bw.ctypes.data, C.addressof(ptrs), C.addressof(ptrs),
+                       2, tw.ctypes.data, C.addressof(ptrs), C.addressof(ptrs), rec.F32, rec.INTERACT_DOT, None, 0)
+    need = L.rec_model_padded_weight_bytes(C.addressof(d))
+    assert need == 64 * 88 * 4
+    h = C.c_void_p(0)
+    d.padded_weights, d.padded_weights_bytes = fake, need - 1
+    assert L.rec_model_create(C.addressof(d), C.addressof(h)) == rec.ERR_WORKSPACE and not h.value
+    d.padded_weights, d.padded_weights_bytes = fake + 8, need
+    assert L.rec_model_create(C.addressof(d), C.addressof(h)) == rec.ERR_WORKSPACE and not h.value      # misaligned
+    d.padded_weights, d.padded_weights_bytes = fake, need
+    assert L.rec_model_create(C.addressof(d), C.addressof(h)) == rec.OK and h.value
+    assert L.rec_model_workspace_bytes(h, 256) > 0
+    assert L.rec_model_forward(h, fake, fake, 0, fake, 4, fake, fake, 1 << 30, None) == rec.ERR_BAD_SHAPE   # not prepared
+    L.rec_model_destroy(h)

@@ -268,6 +268,11 @@ def test_model_forward_small(rec, name, R, B):
     assert_close(np.concatenate(pieces), want, TOL_BF16 if cfg.bf16 else TOL_F32, f"split model {name}")
     # deterministic
     assert np.array_equal(got, model.forward(db.dense, db.indices, db.lengths, B).cpu().numpy())
+    # host-only create: the padded copy of the first predictor layer in a caller-provided buffer, filled by
+    # rec_model_prepare, gives the same bits as the copy rec_model_create allocates itself
+    other = workload.device_model(cfg, tables=model.tables, caller_padded_weights=True)
+    assert (other._padded is not None) == (model.padded_weight_bytes > 0)
+    assert np.array_equal(got, other.forward(db.dense, db.indices, db.lengths, B).cpu().numpy())
 
 
 CONCAT_VARIANTS = {
