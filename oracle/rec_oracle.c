@@ -369,8 +369,8 @@ double orc_max_qps(const double* unit_arrival, const double* service, int64_t n,
 }
 
 /* Batch-size hill climb (Section IV-C): start at the first candidate (unit batch size) and move
- * to the next larger one until the achievable QPS degrades, i.e. stop at the first step that
- * lowers it (a step that leaves it unchanged, such as one between two batch sizes that both miss
+ * to the next larger one as long as the sustainable query rate does not drop: stop at the first
+ * step that lowers it (a step that leaves it unchanged, such as one between two batch sizes that both miss
  * the latency target, is taken).  qps[i] = achievable QPS with the i-th candidate batch size.
  * Returns the index kept. */
 int64_t orc_hill_climb(const double* qps, int64_t n_candidates) {

@@ -15,7 +15,13 @@
 #include <thread>
 #include <vector>
 
+// REC_HOST_ONLY: build just the host-side functions (rec_sched_*) with a plain C++ compiler -- no HIP
+// headers, no device calls -- so that they can run under the host sanitizers.
+#ifdef REC_HOST_ONLY
+#include "rec.h"
+#else
 #include "rec_common.h"
+#endif
 
 namespace {
 
@@ -101,12 +107,15 @@ bool two_tier_args_ok(const int64_t* size, int64_t n, int64_t tau, int64_t batch
 
 }  // namespace
 
+#ifndef REC_HOST_ONLY
 struct rec_stream_pool {
     std::vector<hipStream_t> streams;
 };
+#endif
 
 extern "C" {
 
+#ifndef REC_HOST_ONLY
 rec_status rec_stream_pool_create(int32_t n_streams, rec_stream_pool** out) {
     if (!out) return REC_ERR_NULL;
     *out = nullptr;
@@ -147,6 +156,8 @@ rec_status rec_stream_pool_synchronize(const rec_stream_pool* pool) {
         if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
     return REC_OK;
 }
+
+#endif  // REC_HOST_ONLY
 
 double rec_sched_query_service(int64_t n, int64_t batch, const double* table) {
     if (n < 0 || batch < 1 || !table) return kNaN;
@@ -266,6 +277,8 @@ int64_t rec_sched_hill_climb(const double* qps, int64_t n_candidates) {
     }
     return keep;
 }
+
+#ifndef REC_HOST_ONLY
 
 rec_status rec_model_forward_many(const rec_model* m, const rec_request* requests, float* const* prob, int64_t n,
                                   void* const* streams, void* const* workspaces, size_t workspace_bytes,
@@ -432,5 +445,7 @@ rec_status rec_serve_trace_many(const rec_model* m, const rec_request* requests,
     cleanup();
     return st;
 }
+
+#endif  // REC_HOST_ONLY
 
 }  // extern "C"

@@ -46,31 +46,70 @@ class RecError(RuntimeError):
         super().__init__(f"{where}: {status_string(status)}")
 
 
+# Device code is built without packed fp32 arithmetic (v_pk_add/mul/fma_f32).  The switch is a target
+# feature of the device compiler; hipcc hands it to its host pass too, which does not know it and says
+# so ("not a recognized feature for this target") -- harmless.  tests/test_build_flags.py checks on the
+# generated ISA that the device pass honours it.
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
 def build_library(verbose: bool = False) -> str:
     """Compile the HIP sources for gfx950 into librec.so next to this file."""
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-I" + os.path.join(_ROOT, "include"),
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-pthread", "-o", LIB_PATH] + SOURCES
+    cmd = ["hipcc"] + HIPCC_FLAGS + ["-fPIC", "-shared", "-I" + os.path.join(_ROOT, "include"), "-pthread", "-o", LIB_PATH] + SOURCES
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + r.stderr)
     if verbose:
         print(" ".join(cmd))
+        noise = "is not a recognized feature for this target"
+        rest = [l for l in r.stderr.splitlines() if l.strip() and noise not in l and "warning generated" not in l
+                and "warnings generated" not in l]
+        print(f"hipcc: {r.stderr.count(noise)} host-pass notes about '-packed-fp32-ops' (expected), "
+              f"{len(rest)} other lines of compiler output")
+        for l in rest:
+            print("  " + l)
     return LIB_PATH
 
 
 _lib = None
 
 
+class _PartialLibrary:
+    """A library built from part of the sources (REC_LIB_PATH, e.g. the host-only sanitizer build of
+    the serving functions): prototypes of entry points it lacks are set on placeholders and dropped."""
+
+    class _Missing:
+        restype = argtypes = None
+
+    def __init__(self, cdll):
+        self._cdll = cdll
+
+    def __getattr__(self, name):
+        try:
+            return getattr(self._cdll, name)
+        except AttributeError:
+            if name.startswith("rec_"):
+                return _PartialLibrary._Missing()
+            raise
+
+
 def lib():
-    """Load librec.so (building it only if no built library exists)."""
+    """Load librec.so (building it only if no built library exists).  REC_LIB_PATH names another build of
+    the library to load instead (it may hold only some of the entry points)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        build_library()
-    L = C.CDLL(LIB_PATH)
+    override = os.environ.get("REC_LIB_PATH")
+    if override:
+        L = _PartialLibrary(C.CDLL(override))
+    else:
+        if not os.path.exists(LIB_PATH):
+            build_library()
+        elif os.path.getmtime(LIB_PATH) < max(os.path.getmtime(f) for f in SOURCES + [os.path.join(_ROOT, "include", "rec.h")]):
+            import warnings
+            warnings.warn("librec.so is older than its sources: run __graft_entry__.build() (loading the existing build)",
+                          RuntimeWarning)
+        L = C.CDLL(LIB_PATH)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.rec_status_string.restype = C.c_char_p
     L.rec_status_string.argtypes = [C.c_int]
@@ -143,7 +182,8 @@ def lib():
 
 
 def status_string(status: int) -> str:
-    return lib().rec_status_string(status).decode()
+    f = lib().rec_status_string
+    return f(status).decode() if callable(f) else f"status {status}"      # (a partial build may lack the names)
 
 
 def _check(status: int, where: str) -> None:
