@@ -443,20 +443,29 @@ def copy_calibration(cfg, model, rec, torch):
             "memcpy_d2d_bytes": int(src.numel())}
 
 
-def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np):
+def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np, h2d_queries=300):
     """2000 queries, sizes lognormal(4.5, 1.0) clipped to [1, 1000], each split into sub-batches
-    of B and served one after another; latency = first enqueue to completion of the last."""
+    of B and served one after another; latency = first enqueue to completion of the last.
+    Inputs are resident on the device; for the first `h2d_queries` queries the replay is repeated with
+    every sub-batch's inputs copied from pinned host memory first (the `with_h2d` figures)."""
     sizes = synth.lognormal_query_sizes(synth.MASTER_SEED, synth.SWEEP_QUERIES)
     pool = [gen.batch(100 + k, B=1000) for k in range(8)]           # item pools to cut queries from
     res = {}
     prob = torch.empty(1024, dtype=torch.float32, device="cuda")
+    rank = lambda srt, p: float(srt[max(0, int(np.ceil(p * len(srt))) - 1)])
+    stats = lambda lat, total, n_items: {"samples_per_s": float(n_items / total), "latency_ms_p50": rank(np.sort(lat), 0.50) * 1e3,
+                                         "latency_ms_p95": rank(np.sort(lat), 0.95) * 1e3,
+                                         "latency_ms_p99": rank(np.sort(lat), 0.99) * 1e3}
     for Bs in synth.SWEEP_BATCH_SIZES:
         # pre-stage every sub-batch on the device (inputs resident, as for the headline number)
-        staged = []
+        host, staged = [], []
         for q, n in enumerate(sizes.tolist()):
             src = pool[q % len(pool)]
-            staged.append([workload.DeviceBatch(workload.slice_batch(src, cfg.T, s, c))
-                           for s, c in rec.split_query(n, Bs)])
+            parts = [workload.slice_batch(src, cfg.T, s, c) for s, c in rec.split_query(n, Bs)]
+            staged.append([workload.DeviceBatch(b) for b in parts])
+            if q < h2d_queries:
+                host.append([(torch.from_numpy(b.dense).pin_memory(), torch.from_numpy(b.indices).pin_memory(),
+                              torch.from_numpy(b.lengths).pin_memory()) for b in parts])
         lat = np.empty(len(staged))
         for warm in (True, False):
             torch.cuda.synchronize()
@@ -470,11 +479,26 @@ def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np):
                 if warm and q >= 50:
                     break
             total = time.perf_counter() - t_all
-        srt = np.sort(lat)
-        rank = lambda p: float(srt[max(0, int(np.ceil(p * len(srt))) - 1)])
-        res[str(Bs)] = {"samples_per_s": float(sizes.sum() / total), "latency_ms_p50": rank(0.50) * 1e3,
-                        "latency_ms_p95": rank(0.95) * 1e3, "latency_ms_p99": rank(0.99) * 1e3}
-        del staged
+        res[str(Bs)] = stats(lat, total, sizes.sum())
+        # the same replay with the inputs of every sub-batch coming from (pinned) host memory
+        nq = len(host)
+        lat_d, lat_h = np.empty(nq), np.empty(nq)
+        for mode, out_lat in (("dev", lat_d), ("h2d", lat_h)):
+            torch.cuda.synchronize()
+            t_all = time.perf_counter()
+            for q in range(nq):
+                t0 = time.perf_counter()
+                for d, (hd, hi, hl) in zip(staged[q], host[q]):
+                    if mode == "h2d":
+                        d.dense.copy_(hd, non_blocking=True)
+                        d.indices.copy_(hi, non_blocking=True)
+                        d.lengths.copy_(hl, non_blocking=True)
+                    model.forward(d.dense, d.indices, d.lengths, d.B, prob=prob, workspace=ws)
+                torch.cuda.synchronize()
+                out_lat[q] = time.perf_counter() - t0
+            tot = time.perf_counter() - t_all
+            res[str(Bs)]["first_%d_queries_%s" % (nq, "resident" if mode == "dev" else "with_h2d")] = stats(out_lat, tot, sizes[:nq].sum())
+        del staged, host
     return res
 
 
