@@ -236,7 +236,7 @@ def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384))
     both = {"us": bottom["us"] + top["us"], "flops": bottom["flops"] + top["flops"]}
     both["tflops"] = both["flops"] / both["us"] / 1e6
     both["frac"] = both["tflops"] / MFMA_BF16_PEAK_TFLOPS
-    return {"bound": "mfma", "kernel": "prepare_bf16_kernel + gemm_bf16_ks_kernel / gemm_bf16_kernel", "achieved": l1["tflops"],
+    return {"bound": "mfma", "kernel": "prepare_bf16_kernel + gemm_ks_kernel (64x64 tiles) or gemm_bf16_kernel (128x128, 256x256 tiles)", "achieved": l1["tflops"],
             "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": l1["frac"], "traffic": None, "us_per_launch": l1["us"],
             "flops_per_launch": l1["flops"],
             "layer": f"{cfg.B}x{F} . ({n1}x{F})^T bf16 operands, fp32 accumulate; fp32 in and out through rec_mlp_forward",
