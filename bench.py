@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--repeats", type=int, default=5, help="the timed block of --steps steps is run this often; the median is reported")
     ap.add_argument("--only-sls", action="store_true",
                     help="set-up, then only launches of the pooling kernel (workload's indices, then uniform ones): for counter runs")
+    ap.add_argument("--only-per-batch-size", action="store_true",
+                    help="set-up, then only the whole-forward runs at sub-batch sizes 16/64/256/1024: for kernel traces")
     ap.add_argument("--only-mfma", action="store_true",
                     help="only the bf16 FC layers of the MLP-dominated model at batch 1024 / 4096 / 16384: for counter runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -243,6 +245,27 @@ def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384))
             "batch_sweep": sweep, "stacks": {"bottom": bottom, "top": top, "both": both}}
 
 
+def per_batch_size(cfg, model, host_batches, probs, ws, streams, a, torch, rec, synth, workload):
+    """samples/s of the whole forward per sub-batch size (the batch sizes of the query-size sweep)."""
+    per_b = {}
+    for Bs in synth.SWEEP_BATCH_SIZES:
+        if Bs > cfg.B or a.no_per_batch_size:
+            continue
+        subs = [workload.DeviceBatch(workload.slice_batch(host_batches[k % len(host_batches)], cfg.T, 0, Bs))
+                for k in range(4)]
+
+        def sub_step(i, subs=subs, Bs=Bs):
+            d = subs[i % len(subs)]
+            model.forward(d.dense, d.indices, d.lengths, Bs, prob=probs[0], workspace=ws)
+
+        s1 = time_steps(sub_step, max(50, a.steps // 2), 10, torch)
+        s = median(time_many(model, rec, subs, [probs[0][:Bs].clone() for _ in subs], streams, max(50, a.steps // 2), 10,
+                             torch, repeats=3)) if a.streams > 1 else s1
+        per_b[str(Bs)] = {"samples_per_s": Bs / s, "us_per_batch": s * 1e6,
+                          "single_stream": {"samples_per_s": Bs / s1, "us_per_batch": s1 * 1e6}}
+    return per_b
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -290,6 +313,11 @@ def main():
         if a.copy_calibration:
             out["copy_calibration"] = copy_calibration(cfg, model, rec, torch)
         print(json.dumps(out))
+        return
+
+    if a.only_per_batch_size:
+        print(json.dumps({"per_batch_size": per_batch_size(cfg, model, host_batches, probs, ws, streams, a, torch, rec, synth,
+                                                           workload)}))
         return
 
     def step(i):
@@ -344,23 +372,7 @@ def main():
                        "peak_tflops": peak_tf,
                        "frac": sum(s["flops"] for s in both) / sum(s["us"] for s in both) / 1e6 / peak_tf}
 
-    # samples/s per sub-batch size (the batch sizes of the query-size sweep)
-    per_b = {}
-    for Bs in synth.SWEEP_BATCH_SIZES:
-        if Bs > cfg.B or a.no_per_batch_size:
-            continue
-        subs = [workload.DeviceBatch(workload.slice_batch(host_batches[k % len(host_batches)], cfg.T, 0, Bs))
-                for k in range(4)]
-
-        def sub_step(i, subs=subs, Bs=Bs):
-            d = subs[i % len(subs)]
-            model.forward(d.dense, d.indices, d.lengths, Bs, prob=probs[0], workspace=ws)
-
-        s1 = time_steps(sub_step, max(50, a.steps // 2), 10, torch)
-        s = median(time_many(model, rec, subs, [probs[0][:Bs].clone() for _ in subs], streams, max(50, a.steps // 2), 10,
-                             torch, repeats=3)) if a.streams > 1 else s1
-        per_b[str(Bs)] = {"samples_per_s": Bs / s, "us_per_batch": s * 1e6,
-                          "single_stream": {"samples_per_s": Bs / s1, "us_per_batch": s1 * 1e6}}
+    per_b = per_batch_size(cfg, model, host_batches, probs, ws, streams, a, torch, rec, synth, workload)
 
     metric = ("samples/sec per batch size + SLS achieved HBM GB/s (RMC2-shaped, 1 GPU)" if cfg.name == "rmc2"
               else f"samples/sec per batch size ({cfg.name}-shaped, 1 GPU)")
