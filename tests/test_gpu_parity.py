@@ -190,7 +190,8 @@ def test_interact_vs_oracle(rec, V, D, B):
                                       ((20, 24, 28, 32, 36, 40, 3), 50), ((64, 32, 1000, 16), 40),
                                       ((512, 512, 7), 17), ((600, 64, 700, 5), 33),
                                       ((320, 8), 33), ((448, 40, 17), 20), ((192, 100), 16), ((384, 24), 5),
-                                      ((896, 512), 1024), ((512, 700), 900), ((256, 1024, 8), 1500), ((288, 130), 2100)])
+                                      ((896, 512), 1024), ((512, 700), 900), ((256, 1024, 8), 1500), ((288, 130), 2100),
+                                      ((256, 16424), 3), ((512, 12800, 5), 1)])
 def test_mlp_f32_vs_oracle(rec, widths, B):
     p = synth.mlp_params(widths, stack=3)
     x = rng.uniform(0, 1, size=(B, widths[0])).astype(np.float32)
@@ -216,7 +217,8 @@ def test_mlp_f32_exact_cases(rec):
                                       ((100, 70, 3), 65), ((20, 24, 28, 32, 36, 40, 3), 50),
                                       ((64, 32, 1100, 16), 40), ((1024, 128, 9), 17),
                                       ((512, 700), 600), ((512, 1024, 640, 8), 900), ((2560, 1024), 1024),
-                                      ((640, 8), 33), ((1024, 40, 17), 20), ((896, 100), 16)])
+                                      ((640, 8), 33), ((1024, 40, 17), 20), ((896, 100), 16),
+                                      ((256, 16424), 3), ((256, 8200, 9), 1), ((320, 16424), 70)])
 def test_mlp_bf16_vs_oracle(rec, widths, B):
     oracle.set_threads(16)
     p = synth.mlp_params(widths, stack=4)
