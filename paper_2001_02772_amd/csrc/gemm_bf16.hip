@@ -1,4 +1,5 @@
-// Large bf16 FC layers: C = act(A W^T + b) with A [M x K], W [N x K] bf16, fp32 accumulate.
+// Large FC layers on the matrix cores: C = act(A W^T + b) with A [M x K], W [N x K], fp32 accumulate; bf16 operands
+// on every tile shape, fp32 operands on the small-tile kernel.
 //
 // This is the one genuinely dense, FLOP-heavy contraction of the models in Table I of the
 // DeepRecSys paper: the first Dense-FC layer of the MLP-dominated DLRM-RMC3 (thousands of dense
