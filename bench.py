@@ -210,17 +210,18 @@ def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch
     return r
 
 
-def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384)):
-    """The FC layers of the MLP-dominated model (rmc3 shape: 2560-1024-256-32 and 87-512-256-1, bf16
-    operands, fp32 accumulate) through rec_mlp_forward with resident random inputs: the first (widest)
-    layer alone at several batch sizes and both stacks at the model's batch.  Every figure is all-in:
-    fp32 activations in, the bf16 copy, the matrix kernel(s), fp32 out."""
-    cfg = synth.CONFIGS["rmc3"]
+def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384), workload="rmc3"):
+    """The FC layers of an MLP-dominated model (rmc3 shape: 2560-1024-256-32 and 87-512-256-1; wnd shape:
+    2048-1024-512-256-1; bf16 operands, fp32 accumulate) through rec_mlp_forward with resident random
+    inputs: the first (widest) layer alone at several batch sizes and the stacks at the model's batch.
+    Every figure is all-in: fp32 activations in, the bf16 copy, the matrix kernel(s), fp32 out."""
+    cfg = synth.CONFIGS[workload]
     pb, pt = synth.mlp_params(cfg.bottom, 0), synth.mlp_params(cfg.top, 1)
     dev = lambda a: torch.from_numpy(a).cuda()
     Wb, bb = [rec.f32_to_bf16(dev(w)) for w in pb.W], [dev(v) for v in pb.b]
     Wt, bt = [rec.f32_to_bf16(dev(w)) for w in pt.W], [dev(v) for v in pt.b]
-    F, n1 = cfg.bottom[0], cfg.bottom[1]
+    first_W, first_b = (Wb, bb) if Wb else (Wt, bt)           # a model without a dense stack: its first predictor layer
+    F, n1 = first_W[0].shape[1], first_W[0].shape[0]
 
     def run(Ws, bs, B, final_act, n):
         widths = [Ws[0].shape[1]] + [w.shape[0] for w in Ws]
@@ -232,9 +233,11 @@ def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384))
         fl = 2.0 * B * sum(widths[l] * widths[l + 1] for l in range(len(Ws)))
         return {"us": sec * 1e6, "flops": fl, "tflops": fl / sec / 1e12, "frac": fl / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
-    sweep = {str(B): run(Wb[:1], bb[:1], B, rec.ACT_RELU, steps if B <= 4096 else max(20, steps // 4)) for B in batches}
+    sweep = {str(B): run(first_W[:1], first_b[:1], B, rec.ACT_RELU, steps if B <= 4096 else max(20, steps // 4)) for B in batches}
     l1 = sweep[str(cfg.B)]
-    bottom, top = run(Wb, bb, cfg.B, rec.ACT_RELU, steps), run(Wt, bt, cfg.B, rec.ACT_SIGMOID, steps)
+    zero = {"us": 0.0, "flops": 0.0, "tflops": 0.0, "frac": 0.0}
+    bottom = run(Wb, bb, cfg.B, rec.ACT_RELU, steps) if Wb else zero
+    top = run(Wt, bt, cfg.B, rec.ACT_SIGMOID, steps)
     both = {"us": bottom["us"] + top["us"], "flops": bottom["flops"] + top["flops"]}
     both["tflops"] = both["flops"] / both["us"] / 1e6
     both["frac"] = both["tflops"] / MFMA_BF16_PEAK_TFLOPS
@@ -392,10 +395,8 @@ def main():
            "sls_gbs": sls_gbs, "per_batch_size": per_b, "fc_stacks": stacks, "setup_s": setup_s}
     if cfg.bf16:
         # MLP-dominated workload: the dominant kernel is the first (widest) Dense-FC layer
-        out["roofline"] = mfma_roofline(rec, synth, torch, a.steps, a.warmup) if cfg.name == "rmc3" else None
+        out["roofline"] = mfma_roofline(rec, synth, torch, a.steps, a.warmup, workload=cfg.name)
         out["sls_roofline"] = roofline
-        if out["roofline"] is None:
-            out["roofline"] = roofline
     else:
         out["roofline"] = roofline
     if uniform:
