@@ -68,6 +68,7 @@ def parse():
                     help="also time the steps with every batch's inputs copied from pinned host memory")
     ap.add_argument("--sched", action="store_true",
                     help="also tune the request batch size by hill climbing on latency-bounded throughput")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the query-size sweep that the rmc2 run includes by default")
     ap.add_argument("--sweep", action="store_true",
                     help="also replay 2000 lognormal-sized queries split into sub-batches of 16/64/256/1024")
     return ap.parse_args()
@@ -408,8 +409,11 @@ def main():
     if a.copy_calibration:
         out["copy_calibration"] = copy_calibration(cfg, model, rec, torch)
 
-    if a.sweep:
-        out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np)
+    if a.sweep or (cfg.name == "rmc2" and not a.no_sweep):
+        # the query-size sweep workload (2000 lognormal-sized queries cut into sub-batches of 16/64/256/1024);
+        # host-to-device columns only on request, they need pinned copies of the inputs
+        out["query_sweep"] = query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np,
+                                        h2d_queries=300 if (a.sweep or a.h2d) else 0)
 
     if a.h2d:
         out["h2d_inclusive"] = h2d_inclusive(cfg, model, host_batches, streams, a.steps, a.warmup, torch)
@@ -496,7 +500,7 @@ def query_sweep(cfg, model, gen, ws, torch, rec, synth, workload, np, h2d_querie
         # the same replay with the inputs of every sub-batch coming from (pinned) host memory
         nq = len(host)
         lat_d, lat_h = np.empty(nq), np.empty(nq)
-        for mode, out_lat in (("dev", lat_d), ("h2d", lat_h)):
+        for mode, out_lat in ((("dev", lat_d), ("h2d", lat_h)) if nq else ()):
             torch.cuda.synchronize()
             t_all = time.perf_counter()
             for q in range(nq):
