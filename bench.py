@@ -173,7 +173,7 @@ def cpu_baseline(cfg, batch):
             "single_thread_value": batch.B / (sum(singles) / len(singles))}, p_all
 
 
-def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch, np, workload_name):
+def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch, np, workload_name, min_launches=100):
     """The fused gather-and-pool kernel alone between two events on its launch stream, over the given
     batches.  `achieved` / `frac` count only bytes that cross the memory side of the L2s (request
     counters of a tracked profile, else the compulsory bytes a batch cannot avoid), so the fraction is
@@ -188,6 +188,7 @@ def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch
         rec.sls_forward_offsets(model_tables, d.indices, offs[i % len(dbs)], d.B, out=vecs[:, 1:, :],
                                 out_stride_b=V * cfg.D, out_stride_t=cfg.D)
 
+    steps = max(steps, min_launches)            # kernel-only timing is cheap: the full run never takes fewer than 100 launches
     sec = event_time(sls_only, steps, warmup, torch)
     used = [dbs[i % len(dbs)].n_indices for i in range(steps)]
     alg = float(np.mean([sls_algorithmic_bytes(cfg, n, cfg.B) for n in used]))
@@ -211,7 +212,7 @@ def sls_roofline(cfg, rec, model_tables, dbs, host_batches, steps, warmup, torch
     return r
 
 
-def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384), workload="rmc3"):
+def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384), workload="rmc3", min_launches=100):
     """The FC layers of an MLP-dominated model (rmc3 shape: 2560-1024-256-32 and 87-512-256-1; wnd shape:
     2048-1024-512-256-1; bf16 operands, fp32 accumulate) through rec_mlp_forward with resident random
     inputs: the first (widest) layer alone at several batch sizes and the stacks at the model's batch.
@@ -234,6 +235,7 @@ def mfma_roofline(rec, synth, torch, steps, warmup, batches=(1024, 4096, 16384),
         fl = 2.0 * B * sum(widths[l] * widths[l + 1] for l in range(len(Ws)))
         return {"us": sec * 1e6, "flops": fl, "tflops": fl / sec / 1e12, "frac": fl / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
+    steps = max(steps, min_launches)            # layer-only timing: the full run never takes fewer than 100 launches (a quarter at the largest batch)
     sweep = {str(B): run(first_W[:1], first_b[:1], B, rec.ACT_RELU, steps if B <= 4096 else max(20, steps // 4)) for B in batches}
     l1 = sweep[str(cfg.B)]
     zero = {"us": 0.0, "flops": 0.0, "tflops": 0.0, "frac": 0.0}
@@ -288,7 +290,7 @@ def main():
     pool = rec.StreamPool(a.streams)
     streams = pool.streams
     if a.only_mfma:
-        print(json.dumps({"mfma_roofline": mfma_roofline(rec, synth, torch, a.steps, a.warmup)}))
+        print(json.dumps({"mfma_roofline": mfma_roofline(rec, synth, torch, a.steps, a.warmup, min_launches=0)}))
         return
     cfg = synth.CONFIGS[a.workload]
     t_setup = time.perf_counter()
@@ -310,10 +312,10 @@ def main():
         uniform = (ucfg, [workload.DeviceBatch(b) for b in uhost], uhost)
 
     if a.only_sls:
-        out = {"roofline": sls_roofline(cfg, rec, model.tables, dbs, host_batches, a.steps, a.warmup, torch, np, cfg.name)}
+        out = {"roofline": sls_roofline(cfg, rec, model.tables, dbs, host_batches, a.steps, a.warmup, torch, np, cfg.name, min_launches=0)}
         if uniform:
             out["roofline_uniform"] = sls_roofline(uniform[0], rec, model.tables, uniform[1], uniform[2], a.steps, a.warmup,
-                                                   torch, np, "rmc2-uniform")
+                                                   torch, np, "rmc2-uniform", min_launches=0)
         if a.copy_calibration:
             out["copy_calibration"] = copy_calibration(cfg, model, rec, torch)
         print(json.dumps(out))
